@@ -1,0 +1,10 @@
+"""CPU oracle of the PALSGD update path: TEST INFRASTRUCTURE ONLY.
+
+Only tests/, the smoke check and the benchmark's cpu_baseline leg may import
+this package.  The product path (paper_2504_18454_amd) never does.
+"""
+from .binding import (OracleState, adamw, draw, get_threads, mix, outer,
+                      set_threads, sgdm, u24)
+
+__all__ = ["OracleState", "adamw", "draw", "get_threads", "mix", "outer",
+           "set_threads", "sgdm", "u24"]

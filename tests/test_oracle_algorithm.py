@@ -1,0 +1,329 @@
+"""Pins for the oracle's whole-algorithm driver (Alg. 1) against formulations written
+separately from it, and against the reductions the paper fixes:
+
+  * p = 0 (the mixing branch never fires) is DiLoCo; with OuterOPT = SGD, step size 1, it
+    is Local SGD / FedAvg (Sec. 5.2 "Preliminary Experiments"; Sec. 2.3);
+  * H = 1 with OuterOPT = SGD step size 1 is synchronous averaging, and with plain SGD
+    inside it is one SGD step on the averaged gradient, i.e. DDP (Sec. 3.1);
+  * K = 1 with that OuterOPT leaves the single worker untouched;
+  * in expectation over the branch draw one local step moves x_k by
+    -alpha (grad F + eta (x_k - x)) (App. A.2, the expression for the expected update);
+  * Theorem 1's parameter choice (SGD / SGD step 1, eta = p / (2 H alpha)) contracts on a
+    strongly convex quadratic.
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_18454_amd.workloads import flat_layout
+
+f32 = np.float32
+F = lambda v: float(f32(v))
+
+
+def _state(oracle_mod, K, x0, numels, **kw):
+    offs, row = flat_layout(numels)
+    assert row == x0.size
+    return oracle_mod.OracleState(K, x0, offs, numels, **kw)
+
+
+def _padded(rng, numels, scale=1.0):
+    offs, row = flat_layout(numels)
+    a = np.zeros(row, f32)
+    for o, n in zip(offs, numels):
+        a[o:o + n] = (scale * rng.standard_normal(n)).astype(f32)
+    return a
+
+
+class BruteForce:
+    """Second formulation of Alg. 1, per worker and per scalar element, in Python floats
+    (IEEE double) with fp32 rounding on store.  Written in other algebraic forms than the
+    C oracle: EMA form of the mix, 'decay first, then step_size * m / denom' form of AdamW,
+    delta accumulated as mean of differences."""
+
+    def __init__(self, K, x0, numels, wd_mult, inner, hp, seed):
+        self.K, self.hp, self.inner, self.seed = K, hp, inner, seed
+        offs, _ = flat_layout(numels)
+        self.elems = [(o + i, (wd_mult[j] if wd_mult is not None else 1.0))
+                      for j, (o, n) in enumerate(zip(offs, numels)) for i in range(n)]
+        self.x = [[float(v) for v in x0] for _ in range(K)]
+        self.m = [[0.0] * len(x0) for _ in range(K)]
+        self.v = [[0.0] * len(x0) for _ in range(K)]
+        self.xg = [float(v) for v in x0]
+        self.om = [0.0] * len(x0)
+        self.tau = [0] * K
+
+    @staticmethod
+    def r(v):
+        return float(f32(v))
+
+    def bernoulli(self, t, k):
+        M = 2 ** 64
+        z = (self.seed + (t * self.K + k + 1) * 0x9E3779B97F4A7C15) % M
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) % M
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) % M
+        z ^= z >> 31
+        b = ((z >> 40) + 1) / 2 ** 24          # b in (0, 1] on the 2^-24 grid
+        return b <= int(self.hp["p"] * 2 ** 24) / 2 ** 24
+
+    def iteration(self, t, alpha, eta, G):
+        hp = self.hp
+        for k in range(self.K):
+            if self.bernoulli(t, k):
+                beta = alpha * eta / hp["p"]
+                for i in range(len(self.xg)):
+                    self.x[k][i] = self.r((1 - beta) * self.x[k][i] + beta * self.xg[i])
+            else:
+                lr = alpha / (1 - hp["p"])
+                self.tau[k] += 1
+                tau = self.tau[k]
+                for i, wdm in self.elems:
+                    g = float(G[k][i])
+                    wd = hp["wd"] * wdm
+                    if self.inner == "adamw":
+                        m = hp["b1"] * self.m[k][i] + (1 - hp["b1"]) * g
+                        v = hp["b2"] * self.v[k][i] + (1 - hp["b2"]) * g * g
+                        denom = v ** 0.5 / (1 - hp["b2"] ** tau) ** 0.5 + hp["eps"]
+                        step_size = lr / (1 - hp["b1"] ** tau)
+                        x = self.x[k][i] * (1 - lr * wd) - step_size * m / denom
+                        self.m[k][i], self.v[k][i], self.x[k][i] = self.r(m), self.r(v), self.r(x)
+                    else:
+                        buf = hp["mu"] * self.m[k][i] + g + wd * self.x[k][i]
+                        self.x[k][i] = self.r(self.x[k][i] - lr * buf)
+                        self.m[k][i] = self.r(buf)
+        if (t + 1) % hp["H"] == 0:
+            for i in range(len(self.xg)):
+                delta = sum(self.xg[i] - self.x[k][i] for k in range(self.K)) / self.K
+                om = hp["mu_o"] * self.om[i] + delta
+                d = delta + hp["mu_o"] * om if hp["nesterov"] else om
+                self.xg[i] = self.r(self.xg[i] - hp["lr_o"] * d)
+                self.om[i] = self.r(om)
+                for k in range(self.K):
+                    self.x[k][i] = self.xg[i]
+
+
+@pytest.mark.parametrize("K,H,numels,inner,nesterov", [
+    (1, 1, [1], "adamw", True), (2, 2, [1], "sgdm", True), (2, 3, [3], "adamw", False),
+    (3, 2, [5, 17], "adamw", True), (3, 3, [17, 1, 3], "sgdm", False), (2, 1, [5], "sgdm", True),
+])
+def test_brute_force_tiny(oracle_mod, K, H, numels, inner, nesterov):
+    rng = np.random.default_rng(100 + K * 7 + H)
+    offs, row = flat_layout(numels)
+    x0 = _padded(rng, numels)
+    wdm = [1.0, 0.0, 2.0][:len(numels)]
+    hp = dict(p=0.3, H=H, b1=F(0.9), b2=F(0.999), eps=F(1e-8), wd=F(0.05), mu=F(0.8),
+              lr_o=F(0.7), mu_o=F(0.9), nesterov=nesterov)
+    seed = 99
+    st = _state(oracle_mod, K, x0, numels, inner=inner, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.05,
+                momentum=0.8, p=0.3, H=H, outer_lr=0.7, outer_momentum=0.9, outer_nesterov=nesterov,
+                seed=seed, wd_mult=wdm)
+    bf = BruteForce(K, x0, numels, wdm, inner, hp, seed)
+    alpha, eta = F(0.01), F(4.0)
+    mixed = 0
+    for t in range(12):
+        G = np.zeros((K, row), f32)
+        for k in range(K):
+            G[k] = _padded(rng, numels)
+        st.G[...] = G
+        mask, synced = st.iteration(t, alpha, eta)
+        bf.iteration(t, alpha, eta, G)
+        mixed += int(mask.sum())
+        assert synced == ((t + 1) % H == 0)
+        for name, got, want in (("X", st.X, bf.x), ("M", st.M, bf.m), ("XG", st.XG[None], [bf.xg]),
+                                ("OM", st.OM[None], [bf.om])):
+            np.testing.assert_allclose(got, np.array(want), rtol=3e-7, atol=1e-9, err_msg=f"{name} t={t}")
+        if inner == "adamw":
+            np.testing.assert_allclose(st.V, np.array(bf.v), rtol=3e-7, atol=1e-12)
+        assert list(st.tau) == bf.tau
+    assert 0 < mixed < 12 * K or K * 12 < 20      # both branches were exercised
+
+
+def _quadratic_grads(X, c, noise):
+    return ((X.astype(np.float64) - c[None]) + noise).astype(f32)
+
+
+def test_p_zero_is_diloco_library_loop(oracle_mod):
+    """p = 0: AdamW workers + Nesterov outer optimizer on Delta, written with library optimizers."""
+    rng = np.random.default_rng(20)
+    K, H, numels, T = 3, 4, [128, 64], 12
+    offs, row = flat_layout(numels)
+    x0 = _padded(rng, numels); c = _padded(rng, numels)
+    st = _state(oracle_mod, K, x0, numels, inner="adamw", p=0.0, H=H, weight_decay=0.01,
+                outer_lr=0.7, outer_momentum=0.9, outer_nesterov=True)
+    glob = torch.nn.Parameter(torch.tensor(x0, dtype=torch.float64))
+    outer = torch.optim.SGD([glob], lr=F(0.7), momentum=F(0.9), nesterov=True)
+    workers = [torch.nn.Parameter(torch.tensor(x0, dtype=torch.float64)) for _ in range(K)]
+    inner = [torch.optim.AdamW([w], lr=F(1e-3), betas=(F(0.9), F(0.999)), eps=F(1e-8), weight_decay=F(0.01))
+             for w in workers]
+    for t in range(T):
+        noise = 0.01 * rng.standard_normal((K, row))
+        G = _quadratic_grads(st.X, c, noise)
+        st.G[...] = G
+        mask, synced = st.iteration(t, 1e-3, 16.0)
+        assert not mask.any()
+        for k in range(K):
+            workers[k].grad = torch.tensor(G[k], dtype=torch.float64)
+            inner[k].step()
+        if (t + 1) % H == 0:
+            glob.grad = glob.detach() - torch.stack([w.detach() for w in workers]).mean(0)
+            outer.step()
+            with torch.no_grad():
+                for w in workers:
+                    w.copy_(glob)
+        # fp32 storage in the oracle vs unrounded float64 in the library loop: a few ulps
+        np.testing.assert_allclose(st.X, torch.stack([w.detach() for w in workers]).numpy(), rtol=0, atol=3e-6)
+        np.testing.assert_allclose(st.XG, glob.detach().numpy(), rtol=0, atol=3e-6)
+    assert st.n_outer == T // H and list(st.tau) == [T] * K
+
+
+def test_p_zero_outer_sgd_is_local_sgd(oracle_mod):
+    """p = 0 and OuterOPT = SGD step size 1: plain periodic averaging (Local SGD / FedAvg)."""
+    rng = np.random.default_rng(21)
+    K, H, numels, T, lr = 4, 3, [64], 9, F(0.05)
+    x0 = _padded(rng, numels); c = _padded(rng, numels)
+    st = _state(oracle_mod, K, x0, numels, inner="sgdm", momentum=0.0, weight_decay=0.0, p=0.0, H=H,
+                outer_lr=1.0, outer_momentum=0.0, outer_nesterov=False)
+    W = np.tile(x0.astype(np.float64), (K, 1))
+    for t in range(T):
+        noise = 0.05 * rng.standard_normal((K, 64))
+        G = _quadratic_grads(st.X, c, noise)
+        st.G[...] = G
+        st.iteration(t, lr, 1.0)
+        W = W - lr * G
+        if (t + 1) % H == 0:
+            W[:] = W.mean(axis=0)
+        np.testing.assert_allclose(st.X, W, rtol=0, atol=2e-6)
+
+
+def test_h_one_is_synchronous_averaging_and_ddp(oracle_mod):
+    """H = 1, outer SGD step 1, plain SGD inside, p = 0: every step equals one SGD step on the
+    mean gradient from a common point (DDP)."""
+    rng = np.random.default_rng(22)
+    K, numels, lr = 5, [32, 3], F(0.1)
+    offs, row = flat_layout(numels)
+    x0 = _padded(rng, numels)
+    st = _state(oracle_mod, K, x0, numels, inner="sgdm", momentum=0.0, weight_decay=0.0, p=0.0, H=1,
+                outer_lr=1.0, outer_momentum=0.0, outer_nesterov=False)
+    x = x0.astype(np.float64)
+    for t in range(8):
+        G = np.stack([_padded(rng, numels) for _ in range(K)])
+        st.G[...] = G
+        _, synced = st.iteration(t, lr, 1.0)
+        assert synced
+        x = x - lr * G.astype(np.float64).mean(axis=0)
+        np.testing.assert_allclose(st.XG, x, rtol=0, atol=1e-6)
+        for k in range(K):
+            assert np.array_equal(st.X[k], st.XG)
+
+
+def test_single_worker_outer_identity_in_the_loop(oracle_mod):
+    rng = np.random.default_rng(23)
+    numels = [48]
+    x0 = _padded(rng, numels)
+    a = _state(oracle_mod, 1, x0, numels, inner="adamw", p=0.0, H=2, outer_lr=1.0, outer_momentum=0.0,
+               outer_nesterov=False)
+    b = _state(oracle_mod, 1, x0, numels, inner="adamw", p=0.0, H=10 ** 6)     # never synchronises
+    for t in range(6):
+        g = _padded(rng, numels)[None]
+        a.G[...] = g; b.G[...] = g
+        a.iteration(t, 1e-3, 1.0); b.iteration(t, 1e-3, 1.0)
+        assert np.array_equal(a.X, b.X)
+
+
+def test_lr_rescale_and_mask_override(oracle_mod):
+    """p > 0 with the mixing branch forced off equals a p = 0 run at learning rate alpha/(1-p)."""
+    rng = np.random.default_rng(24)
+    K, numels, p = 2, [200], 0.25
+    x0 = _padded(rng, numels)
+    for inner in ("adamw", "sgdm"):
+        a = _state(oracle_mod, K, x0, numels, inner=inner, p=p, H=4)
+        b = _state(oracle_mod, K, x0, numels, inner=inner, p=0.0, H=4)
+        alpha = F(1e-3)
+        alpha_b = F(alpha / (1 - p))
+        for t in range(8):
+            G = np.stack([_padded(rng, numels) for _ in range(K)])
+            a.G[...] = G; b.G[...] = G
+            a.iteration(t, alpha, 16.0, mask_override=np.zeros(K, np.uint8))
+            b.iteration(t, alpha_b, 16.0)
+            # alpha/(1-p) is evaluated in double on one side and pre-rounded to fp32 on the other
+            np.testing.assert_allclose(a.X, b.X, rtol=1e-6, atol=1e-9)
+
+
+def test_expected_local_update(oracle_mod):
+    """p * (mix move) + (1-p) * (gradient move) = -alpha (g + eta (x_k - x)) with plain SGD inside:
+    checks the 1/p and 1/(1-p) factors and that no 1/K enters the mixing coefficient."""
+    rng = np.random.default_rng(25)
+    K, numels, p, alpha, eta = 3, [256], 0.125, F(0.01), F(2.0)
+    x0 = _padded(rng, numels)
+    moves = {}
+    for branch in (0, 1):
+        st = _state(oracle_mod, K, x0, numels, inner="sgdm", momentum=0.0, weight_decay=0.0, p=p, H=10 ** 6)
+        st.X[...] = rng.standard_normal(st.X.shape).astype(f32) if branch == 0 else moves["X"]
+        moves.setdefault("X", st.X.copy())
+        st.X[...] = moves["X"]
+        G = np.stack([_padded(np.random.default_rng(77), numels) for _ in range(K)])
+        st.G[...] = G
+        st.local_step(0, alpha, eta, mask_override=np.full(K, branch, np.uint8))
+        moves[branch] = st.X.astype(np.float64) - moves["X"]
+    want = -alpha * (G + eta * (moves["X"].astype(np.float64) - x0[None]))
+    got = p * moves[1] + (1 - p) * moves[0]
+    np.testing.assert_allclose(got, want, rtol=0, atol=2e-7)
+
+
+def test_mix_leaves_inner_optimizer_untouched(oracle_mod):
+    rng = np.random.default_rng(26)
+    K, numels = 4, [96]
+    st = _state(oracle_mod, K, _padded(rng, numels), numels, inner="adamw", p=0.5, H=100)
+    st.G[...] = np.stack([_padded(rng, numels) for _ in range(K)])
+    st.local_step(0, 1e-3, 16.0, mask_override=np.zeros(K, np.uint8))
+    m, v, tau = st.M.copy(), st.V.copy(), st.tau.copy()
+    st.X[...] += f32(0.5)
+    mask = st.local_step(1, 1e-3, 16.0, mask_override=np.array([1, 0, 1, 0], np.uint8))
+    assert list(mask) == [1, 0, 1, 0]
+    assert np.array_equal(st.M[[0, 2]], m[[0, 2]]) and np.array_equal(st.V[[0, 2]], v[[0, 2]])
+    assert list(st.tau) == [1, 2, 1, 2]
+    assert not np.array_equal(st.M[1], m[1])
+
+
+def test_identical_workers_stay_identical_and_permutation(oracle_mod):
+    rng = np.random.default_rng(27)
+    K, numels = 4, [130, 70]
+    offs, row = flat_layout(numels)
+    x0 = _padded(rng, numels)
+    perm = [2, 0, 3, 1]
+    a = _state(oracle_mod, K, x0, numels, p=0.2, H=3)
+    b = _state(oracle_mod, K, x0, numels, p=0.2, H=3)
+    for t in range(7):
+        G = np.stack([_padded(rng, numels) for _ in range(K)])
+        G[1] = G[0]
+        mask = np.array([t % 3 == 1, t % 3 == 1, t % 2 == 0, 0], np.uint8)
+        a.G[...] = G; b.G[...] = G[perm]
+        a.iteration(t, 1e-3, 16.0, mask_override=mask)
+        b.iteration(t, 1e-3, 16.0, mask_override=mask[perm])
+        assert np.array_equal(a.X[0], a.X[1])
+        np.testing.assert_allclose(b.X, a.X[perm], rtol=0, atol=1e-7)   # mean over k differs by rounding order at most
+        pad = np.ones(row, bool)
+        for o, n in zip(offs, numels):
+            pad[o:o + n] = False
+        assert not a.X[:, pad].any() and not a.XG[pad].any()
+
+
+def test_theorem_parameters_contract_on_quadratic(oracle_mod):
+    """SGD inside, SGD step 1 outside, eta = p/(2 H alpha) (Theorem 1): the global model approaches
+    the minimiser of 0.5|x - c|^2, and more workers lower the noise floor."""
+    def run(K, seed):
+        rng = np.random.default_rng(seed)
+        numels, H, p, alpha, T = [256], 8, 0.25, F(0.02), 400
+        x0 = _padded(rng, numels, 3.0); c = _padded(rng, numels)
+        st = _state(oracle_mod, K, x0, numels, inner="sgdm", momentum=0.0, weight_decay=0.0, p=p, H=H,
+                    outer_lr=1.0, outer_momentum=0.0, outer_nesterov=False, seed=seed)
+        eta = F(p / (2 * H * alpha))
+        d0 = np.linalg.norm(x0 - c)
+        for t in range(T):
+            st.G[...] = _quadratic_grads(st.X, c, 0.5 * rng.standard_normal(st.X.shape))
+            st.iteration(t, alpha, eta)
+        return np.linalg.norm(st.XG - c) / d0
+    e2, e16 = run(2, 5), run(16, 5)
+    assert e2 < 0.1 and e16 < e2
