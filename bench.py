@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the PALSGD parameter-update path on one MI355X.
+
+A step is one iteration of Alg. 1 for all K replicas: the fused local update (gradient
+step or pseudo-synchronization step per replica, as the seeded branch draws decide) and,
+when (t+1) mod H == 0, the outer step.  Inputs are synthetic, seeded and already resident
+in HBM when the timed region starts.  Prints ONE JSON line:
+
+  value       K*P*steps / elapsed: replica-parameter updates per second
+  roofline    the fused local-update kernel against the HBM peak: algorithmic bytes per
+              launch (26 B per replica-element on the AdamW/bf16 gradient branch, 28 fp32,
+              20 SGD-momentum, 12 on the mixing branch) over its mean launch duration,
+              measured with HIP events on the launch stream inside the timed region
+  cpu_baseline the CPU oracle timed on a bounded slice of the same workload
+
+    python bench.py [--gpus 1] [--steps 256] [--warmup 64] [--workload gptneo125m_k8]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def grad_bytes_per_elem(inner: str, grad_dtype: str) -> int:
+    g = 4 if grad_dtype == "f32" else 2
+    return (24 if inner == "adamw" else 16) + g          # read+write x,m(,v) + read g
+
+
+def run_gpu(w, steps, warmup, chunk, outer_variant):
+    import torch
+
+    from paper_2504_18454_amd import Palsgd, make_config, palsgd_layout
+    from paper_2504_18454_amd import binding
+
+    binding.lib()                                       # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    cfg = make_config(w.K, w.numels, inner=w.inner, grad_dtype=w.grad_dtype, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
+                      weight_decay=w.weight_decay, momentum=w.momentum, p=w.p, H=w.H, outer_lr=w.outer_lr,
+                      outer_momentum=w.outer_momentum, outer_nesterov=w.outer_nesterov, seed=w.seed)
+    row, offs = palsgd_layout(cfg)
+    K = w.K
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    f = torch.float32
+    x0 = torch.empty(row, dtype=f, device=dev).normal_(0.0, 0.02, generator=gen)
+    pad = torch.ones(row, dtype=torch.bool, device=dev)
+    for o, n in zip(offs, w.numels):
+        pad[o:o + n] = False
+    pad_idx = pad.nonzero().flatten()
+    del pad
+    x0.index_fill_(0, pad_idx, 0.0)
+    X = torch.empty((K, row), dtype=f, device=dev)
+    M = torch.empty((K, row), dtype=f, device=dev)
+    V = torch.empty((K, row), dtype=f, device=dev) if w.inner == "adamw" else None
+    XG = torch.empty(row, dtype=f, device=dev)
+    OM = torch.empty(row, dtype=f, device=dev)
+    G = torch.empty((K, row), dtype=f if w.grad_dtype == "f32" else torch.bfloat16, device=dev)
+    # gradients of 0.5|x - c|^2 at x0 plus noise, generated once (their values do not affect cost)
+    c = torch.empty(row, dtype=f, device=dev).normal_(0.0, 1.0, generator=gen)
+    for k in range(K):
+        g = torch.empty(row, dtype=f, device=dev).normal_(0.0, w.sigma, generator=gen)
+        g.add_(x0).sub_(c)
+        g.index_fill_(0, pad_idx, 0.0)
+        G[k].copy_(g)
+    del g, c
+    stream = torch.cuda.Stream(device=dev)
+    ctx = Palsgd(cfg, X, M, V, G, XG, OM, row, x0=x0, stream=stream)
+    if chunk or outer_variant:
+        ctx.palsgd_set_tuning(chunk, outer_variant)
+    torch.cuda.synchronize()
+
+    def one(t, ev=None):
+        if ev is not None:
+            ev[0].record(stream)
+        ctx.palsgd_step(t, w.alpha, w.eta, None, None, stream)
+        if ev is not None:
+            ev[1].record(stream)
+        if (t + 1) % w.H == 0:
+            ctx.palsgd_outer_step(t, stream)
+            if ev is not None:
+                ev[2].record(stream)
+            return True
+        return False
+
+    for t in range(warmup):
+        one(t)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    masks = [ctx.palsgd_draw(t) for t in range(warmup, warmup + steps)]
+    synced = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        synced.append(one(warmup + i, events[i]))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    P = w.P
+    gb, mb = grad_bytes_per_elem(w.inner, w.grad_dtype), 12
+    step_ms = [events[i][0].elapsed_time(events[i][1]) for i in range(steps)]
+    step_bytes = [float(P) * ((K - int(m.sum())) * gb + int(m.sum()) * mb) for m in masks]
+    outer_ms = [events[i][1].elapsed_time(events[i][2]) for i in range(steps) if synced[i]]
+    outer_bytes = float(P) * (8 * K + 16)
+    total_bytes = sum(step_bytes) + outer_bytes * len(outer_ms)
+    res = dict(
+        elapsed=elapsed, updates=float(K) * P * steps, row=row,
+        step_kernel_ms=float(np.mean(step_ms)), step_kernel_gbps=sum(step_bytes) / (sum(step_ms) * 1e-3) / 1e9,
+        step_kernel_bytes=float(np.mean(step_bytes)),
+        outer_kernel_ms=float(np.mean(outer_ms)) if outer_ms else None,
+        outer_kernel_gbps=(outer_bytes / (np.mean(outer_ms) * 1e-3) / 1e9) if outer_ms else None,
+        n_outer=len(outer_ms), mix_fraction=float(np.mean([m.mean() for m in masks])),
+        blended_gbps=total_bytes / elapsed / 1e9,
+    )
+    torch.cuda.synchronize()
+    ctx.palsgd_destroy()
+    return res
+
+
+def run_cpu_baseline(w, slice_div=8):
+    """The oracle, as it stands, on the first 1/slice_div of every replica row for H+1 steps."""
+    import oracle
+    from paper_2504_18454_amd.workloads import flat_layout, to_bf16_bits
+
+    threads = max(1, min(int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1), os.cpu_count() or 1))
+    oracle.set_threads(threads)
+    offs, row = flat_layout(w.numels)
+    n = max(64, row // slice_div // 64 * 64)
+    rng = np.random.default_rng(w.seed)
+    x0 = (0.02 * rng.standard_normal(n, dtype=np.float32)).astype(np.float32)
+    st = oracle.OracleState(w.K, x0, [0], [n], inner=w.inner, grad_dtype=w.grad_dtype, beta1=w.beta1, beta2=w.beta2,
+                            eps=w.eps, weight_decay=w.weight_decay, momentum=w.momentum, p=w.p, H=w.H,
+                            outer_lr=w.outer_lr, outer_momentum=w.outer_momentum, outer_nesterov=w.outer_nesterov,
+                            seed=w.seed)
+    for k in range(w.K):
+        g = (x0 - rng.standard_normal(n, dtype=np.float32) + np.float32(w.sigma) * rng.standard_normal(n, dtype=np.float32))
+        st.G[k] = g if w.grad_dtype == "f32" else to_bf16_bits(g)
+    steps = w.H + 1
+    st.iteration(0, w.alpha, w.eta)                      # touch every page once
+    t0 = time.perf_counter()
+    for t in range(1, steps + 1):
+        st.iteration(t, w.alpha, w.eta)
+    dt = time.perf_counter() - t0
+    return dict(value=float(w.K) * n * steps / dt, unit="replica-param updates/s", cores=threads, kind="oracle",
+                sample=f"first {n} elements of each of the K={w.K} replica rows (1/{slice_div} of the row), "
+                       f"{steps} steps incl. one outer step, {dt:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--workload", default="gptneo125m_k8")
+    ap.add_argument("--chunk", type=int, default=0, help="elements per workgroup chunk (0 = library default)")
+    ap.add_argument("--outer-variant", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (K replicas share it); --gpus must be 1. "
+              "No multi-GPU figure exists for it.", file=sys.stderr)
+        sys.exit(2)
+    from paper_2504_18454_amd.workloads import workload
+    w = workload(a.workload)
+    r = run_gpu(w, a.steps, a.warmup, a.chunk, a.outer_variant)
+    cpu = None if a.no_cpu_baseline else run_cpu_baseline(w)
+    gb = grad_bytes_per_elem(w.inner, w.grad_dtype)
+    out = {
+        "metric": "replica-param updates/s", "value": r["updates"] / r["elapsed"], "unit": "replica-param updates/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": r["elapsed"] / a.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": a.workload, "K": w.K, "P": w.P, "tensors": len(w.tensors), "inner": w.inner,
+                   "grad_dtype": w.grad_dtype, "p": w.p, "H": w.H, "eta": w.eta, "alpha": w.alpha,
+                   "outer": f"nesterov lr {w.outer_lr} mu {w.outer_momentum}", "outer_steps_timed": r["n_outer"],
+                   "mix_fraction_timed": round(r["mix_fraction"], 4)},
+        "hbm_GBps_whole_step": r["blended_gbps"], "hbm_frac_whole_step": r["blended_gbps"] / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": r["step_kernel_gbps"],
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": r["step_kernel_gbps"] / HBM_PEAK_GBPS,
+                     "traffic": None, "bytes_per_launch": r["step_kernel_bytes"], "ms_per_launch": r["step_kernel_ms"],
+                     "bytes_per_elem": {"grad": gb, "mix": 12}},
+        "outer_kernel": {"ms_per_launch": r["outer_kernel_ms"], "achieved": r["outer_kernel_gbps"], "unit": "GB/s",
+                         "frac": (r["outer_kernel_gbps"] / HBM_PEAK_GBPS) if r["outer_kernel_gbps"] else None,
+                         "bytes_per_elem": 8 * w.K + 16},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,154 @@
+/*
+ * palsgd.h - C ABI of the PALSGD parameter-update path for AMD MI355X (gfx950).
+ *
+ * The library updates K worker replicas of a model that live side by side in one
+ * GPU's memory, following Algorithm 1 of "Pseudo-Asynchronous Local SGD" (PALSGD):
+ * per step either a pseudo-synchronization (mixing) step toward the stale global
+ * model or an InnerOPT gradient step, and every H steps the outer step.
+ *
+ * Data layout (all device memory, caller-owned, fp32 unless noted):
+ *   X [K][row_stride]  local models x_k                      (Sec. 4.1)
+ *   M [K][row_stride]  InnerOPT first moment / momentum buffer
+ *   V [K][row_stride]  InnerOPT second moment (AdamW only; may be NULL for SGDM)
+ *   G [K][row_stride]  gradients g_k, fp32 or bf16, written by the caller before
+ *                      each step                             (Sec. 3, WorkerOPT eq.)
+ *   XG[row_stride]     global model copy x                   (Sec. 4.1)
+ *   OM[row_stride]     OuterOPT momentum buffer              (Sec. 4.3)
+ * A row is the flat concatenation of the model's tensors; every tensor starts at a
+ * multiple of 64 elements (palsgd_layout).  Padding elements must be zero in x0 and
+ * in G; the update keeps them zero.  row_stride >= P_padded, a multiple of 64.
+ * Every base pointer must be 16-byte aligned.
+ *
+ * Ownership: the library borrows the buffer pointers from palsgd_init until
+ * palsgd_destroy and owns only its context and a small device-side table (allocated
+ * by the first call that launches a local update, 16 bytes per chunk of a row).
+ * Streams: `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ * device work is enqueued on it; calls return without waiting.
+ * Errors: every entry point returns a palsgd_status and never aborts; argument
+ * errors are found before any launch and leave all state untouched.  The text of
+ * the last error of a context is available through palsgd_last_error.
+ * Threads: a context must not be used from two threads at once.
+ */
+#ifndef PALSGD_H
+#define PALSGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PALSGD_MAX_K 64u /* largest worker count the paper runs (App. B, CIFAR-10 simulation) */
+
+typedef struct palsgd_ctx palsgd_ctx; /* opaque */
+
+typedef enum {
+    PALSGD_OK = 0,
+    PALSGD_EINVAL = 1, /* bad argument; nothing was launched            */
+    PALSGD_ENOMEM = 2, /* host or device allocation of library state    */
+    PALSGD_EHIP = 3,   /* a HIP call failed; see palsgd_last_error       */
+    PALSGD_ESTATE = 4  /* call not valid in the context's current state */
+} palsgd_status;
+
+typedef enum { PALSGD_INNER_ADAMW = 0, PALSGD_INNER_SGDM = 1 } palsgd_inner_opt;
+typedef enum { PALSGD_GRAD_F32 = 0, PALSGD_GRAD_BF16 = 1 } palsgd_grad_dtype;
+
+/* Inputs of Algorithm 1 plus the constants of the two optimizers (Sec. 4.3). */
+typedef struct {
+    uint32_t K;                   /* workers, 1..PALSGD_MAX_K                               */
+    uint32_t n_tensors;           /* >= 1                                                   */
+    const uint64_t *tensor_numel; /* host array [n_tensors], each >= 1; copied at init      */
+    const float *tensor_wd_mult;  /* host array [n_tensors] or NULL (= 1): per-tensor
+                                     multiplier on weight_decay                             */
+    int32_t inner;                /* palsgd_inner_opt                                       */
+    int32_t grad_dtype;           /* palsgd_grad_dtype                                      */
+    float beta1, beta2, eps;      /* AdamW moments and epsilon                              */
+    float weight_decay;           /* AdamW: decoupled; SGDM: added to the gradient          */
+    float momentum;               /* SGDM momentum (dampening 0, not Nesterov)              */
+    double p;                     /* mixing probability, 0 <= p < 1 (Alg. 1 input)          */
+    uint32_t H;                   /* synchronization interval, >= 1 (Alg. 1 input)          */
+    float outer_lr;               /* OuterOPT learning rate                                 */
+    float outer_momentum;         /* OuterOPT momentum, 0 = plain SGD                       */
+    int32_t outer_nesterov;       /* 1: Nesterov momentum (Sec. 4.3), 0: heavy ball         */
+    uint64_t seed;                /* seed of the branch draws                               */
+} palsgd_config;
+
+typedef struct {
+    float *X, *M, *V; /* device */
+    void *G;          /* device, float or bf16 according to grad_dtype */
+    float *XG, *OM;   /* device */
+    uint64_t row_stride;
+} palsgd_buffers;
+
+/* Flat layout of a row: tensor_offset[j] (host array [n_tensors], may be NULL) is the
+ * start element of tensor j, each start rounded up to a multiple of 64; *P_padded is
+ * the padded row length.  Only K-independent fields of the config are read
+ * (n_tensors, tensor_numel).  EINVAL on NULL pointers, n_tensors == 0 or a zero numel. */
+palsgd_status palsgd_layout(const palsgd_config *cfg, uint64_t *P_padded, uint64_t *tensor_offset);
+
+/* Alg. 1, "x_k^(0) <- x^(0)": creates a context over the caller's buffers.  If x0_dev
+ * (device, P_padded floats, padding zero) is not NULL, it is copied into XG and every
+ * row of X, and M, V, OM are cleared, on `stream`; if NULL the buffers are taken as
+ * they are (resume).  EINVAL: K outside 1..64, H == 0, p outside [0,1), NULL or
+ * misaligned buffers, row_stride < P_padded or not a multiple of 64, beta/eps/momentum
+ * outside their ranges, V == NULL with AdamW.  On failure *out is NULL. */
+palsgd_status palsgd_init(const palsgd_config *cfg, const palsgd_buffers *buf, const float *x0_dev,
+                          void *stream, palsgd_ctx **out);
+
+/* Branch draws b_k^(t) of step t for all K workers (Alg. 1 "b ~ U[0,1]; if b <= p";
+ * App. A.2): mask_out (host, K bytes) gets 1 where worker k takes the mixing step.
+ * Pure function of (seed, t, k): SplitMix64 output function of the counter t*K+k,
+ * top 24 bits compared with floor(p * 2^24).  Host only, no device work. */
+palsgd_status palsgd_draw(const palsgd_ctx *ctx, uint64_t t, uint8_t *mask_out);
+
+/* Gradient step of step t (Alg. 1 "gradient step"; Sec. 4.1 first equation):
+ * x_k <- InnerOPT(x_k, grad_scale[k] * G[k], alpha_t / (1-p)) for every worker whose
+ * draw is 0, and advances that worker's InnerOPT step count.  grad_scale: host array
+ * [K] or NULL (= 1).  mask_override: host array [K] or NULL; if given it replaces the
+ * draws (1 = this worker mixes, so it is skipped here).  One launch; no launch if no
+ * worker takes the branch. */
+palsgd_status palsgd_inner_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, const float *grad_scale,
+                                const uint8_t *mask_override, void *stream);
+
+/* Pseudo-synchronization step of step t (Alg. 1 "pseudo-synchronization step";
+ * Sec. 4.1 second equation): x_k <- x_k - (alpha_t * eta_t / p) (x_k - XG) for every
+ * worker whose draw is 1.  InnerOPT state is not touched.  EINVAL if a worker is to
+ * mix while p == 0 (the coefficient is undefined).  No launch if no worker mixes. */
+palsgd_status palsgd_pseudo_sync(palsgd_ctx *ctx, uint64_t t, float alpha_t, float eta_t,
+                                 const uint8_t *mask_override, void *stream);
+
+/* Both branches of step t in ONE launch: equal to palsgd_inner_step followed by
+ * palsgd_pseudo_sync for the same t (they touch disjoint workers). */
+palsgd_status palsgd_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, float eta_t,
+                          const float *grad_scale, const uint8_t *mask_override, void *stream);
+
+/* Outer step (Alg. 1 "aggregate outer gradient" and "update global model"; Sec. 4.2):
+ * Delta = XG - (1/K) sum_k X[k];  OM <- mu OM + Delta;
+ * XG <- XG - outer_lr (Delta + mu OM) (Nesterov) or XG - outer_lr OM;  X[k] <- XG for
+ * all k (Sec. 2.1: workers restart from the global model).  The caller decides when
+ * ((t+1) mod H == 0 in Alg. 1); t is recorded for diagnostics only. */
+palsgd_status palsgd_outer_step(palsgd_ctx *ctx, uint64_t t, void *stream);
+
+/* Host-side scalar state for checkpoint / resume: tau[k] = gradient steps worker k
+ * has taken (drives AdamW's bias correction), n_outer = outer steps taken. */
+palsgd_status palsgd_get_state(const palsgd_ctx *ctx, uint64_t *tau, uint64_t *n_outer);
+palsgd_status palsgd_set_state(palsgd_ctx *ctx, const uint64_t *tau, uint64_t n_outer);
+
+/* Text of the last error recorded in ctx ("" if none).  With ctx == NULL: the text of
+ * the last error of a call that had no context (palsgd_layout, palsgd_init). */
+const char *palsgd_last_error(const palsgd_ctx *ctx);
+
+/* Frees the context and the library's device table (waits for nothing: the caller
+ * must have synchronised work that still uses the table).  NULL is accepted. */
+void palsgd_destroy(palsgd_ctx *ctx);
+
+/* Launch-shape knobs for tuning and tests: elements per workgroup chunk (multiple of
+ * 2048, <= 65536; 0 = default) and outer-kernel variant (0 = default choice,
+ * 1 = per-lane walk over k, 2 = replicas split over the workgroup's waves with partial
+ * sums staged through LDS).  EINVAL on other values. */
+palsgd_status palsgd_set_tuning(palsgd_ctx *ctx, uint32_t chunk_elems, uint32_t outer_variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PALSGD_H */

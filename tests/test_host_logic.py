@@ -1,0 +1,127 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its host logic (layout, argument validation, branch draws, scalar state) behaves as
+include/palsgd.h says.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2504_18454_amd import binding
+from paper_2504_18454_amd.binding import Buffers, lib, make_config, palsgd_layout
+from paper_2504_18454_amd.workloads import WORKLOADS, flat_layout, workload
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "palsgd.h")
+FAKE = 4096  # a 16-byte aligned non-NULL address; never dereferenced on the host
+
+
+def _declared():
+    text = open(HEADER).read()
+    return sorted(set(re.findall(r"\b(palsgd_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert set(binding.EXPORTS) == set(names)
+    for n in names:
+        assert hasattr(lib(), n), n
+
+
+def test_layout_pads_to_64_and_matches_generator_layout():
+    for name in WORKLOADS:
+        w = workload(name)
+        P, offs = palsgd_layout(make_config(w.K, w.numels))
+        goffs, grow = flat_layout(w.numels)
+        assert (P, offs) == (grow, goffs)
+        assert all(o % 64 == 0 for o in offs) and P % 64 == 0 and P >= w.P
+    assert palsgd_layout(make_config(1, [1])) == (64, [0])
+    assert palsgd_layout(make_config(1, [64, 65, 1])) == (256, [0, 64, 192])
+
+
+def _init(cfg, **over):
+    b = dict(X=FAKE, M=FAKE, V=FAKE, G=FAKE, XG=FAKE, OM=FAKE, row_stride=palsgd_layout(cfg)[0])
+    b.update(over)
+    out = C.c_void_p()
+    st = lib().palsgd_init(C.byref(cfg), C.byref(Buffers(**b)), None, None, C.byref(out))
+    return st, out
+
+
+def test_init_rejects_bad_arguments_without_touching_the_device():
+    bad = [
+        dict(cfg=dict(K=0)), dict(cfg=dict(K=65)), dict(cfg=dict(H=0)), dict(cfg=dict(p=1.0)), dict(cfg=dict(p=-0.1)),
+        dict(cfg=dict(beta1=1.0)), dict(cfg=dict(beta2=-0.1)), dict(cfg=dict(eps=float("nan"))),
+        dict(cfg=dict(inner="sgdm", momentum=1.0)), dict(cfg=dict(outer_momentum=1.5)),
+        dict(cfg=dict(outer_lr=float("inf"))), dict(cfg=dict(weight_decay=-1.0)),
+        dict(cfg=dict(wd_mult=[1.0, float("nan")])),
+        dict(buf=dict(X=None)), dict(buf=dict(V=None)), dict(buf=dict(G=FAKE + 4)), dict(buf=dict(row_stride=64)),
+        dict(buf=dict(row_stride=128 + 32)),
+    ]
+    for case in bad:
+        kw = dict(K=4)
+        kw.update(case.get("cfg", {}))
+        K = kw.pop("K")
+        cfg = make_config(K, [100, 7], **kw)
+        st, out = _init(cfg, **case.get("buf", {}))
+        assert st == binding.PALSGD_EINVAL, case
+        assert not out.value
+        assert b"palsgd_init" in lib().palsgd_last_error(None)
+    # empty model and zero-sized tensor
+    for numels in ([], [5, 0]):
+        cfg = make_config(2, numels)
+        P = C.c_uint64()
+        assert lib().palsgd_layout(C.byref(cfg), C.byref(P), None) == binding.PALSGD_EINVAL
+    # SGD-momentum needs no V
+    st, out = _init(make_config(2, [10], inner="sgdm"), V=None)
+    assert st == binding.PALSGD_OK
+    lib().palsgd_destroy(out)
+
+
+def test_draws_equal_oracle_bit_for_bit(oracle_mod):
+    for K, p, seed in ((4, 0.1, 0), (8, 0.05, 1), (16, 0.02, 3), (64, 0.25, 2 ** 63 + 5), (1, 0.5, 9), (3, 0.0, 4)):
+        st, ctx = _init(make_config(K, [128], p=p, seed=seed))
+        assert st == 0
+        mask = np.zeros(K, np.uint8)
+        for t in list(range(300)) + [2 ** 40 + 7, 2 ** 62]:
+            assert lib().palsgd_draw(ctx, t, mask.ctypes.data_as(C.POINTER(C.c_uint8))) == 0
+            want = [oracle_mod.draw(seed, t, k, K, p) for k in range(K)]
+            assert list(mask) == want, (K, p, seed, t)
+        lib().palsgd_destroy(ctx)
+
+
+def test_state_roundtrip_and_step_argument_errors():
+    st, ctx = _init(make_config(3, [128], p=0.0))
+    assert st == 0
+    tau = (C.c_uint64 * 3)(5, 6, 7)
+    assert lib().palsgd_set_state(ctx, tau, 9) == 0
+    got = (C.c_uint64 * 3)()
+    n = C.c_uint64()
+    assert lib().palsgd_get_state(ctx, got, C.byref(n)) == 0
+    assert list(got) == [5, 6, 7] and n.value == 9
+    # argument errors are reported before anything is launched
+    assert lib().palsgd_step(ctx, 0, float("nan"), 1.0, None, None, None) == binding.PALSGD_EINVAL
+    assert lib().palsgd_step(ctx, 0, -1.0, 1.0, None, None, None) == binding.PALSGD_EINVAL
+    assert lib().palsgd_pseudo_sync(ctx, 0, 1e-3, float("inf"), None, None) == binding.PALSGD_EINVAL
+    force_mix = (C.c_uint8 * 3)(0, 1, 0)
+    assert lib().palsgd_step(ctx, 0, 1e-3, 16.0, None, force_mix, None) == binding.PALSGD_EINVAL   # p == 0
+    assert b"p == 0" in lib().palsgd_last_error(ctx)
+    gs = (C.c_float * 3)(1.0, float("nan"), 1.0)
+    assert lib().palsgd_inner_step(ctx, 0, 1e-3, gs, (C.c_uint8 * 3)(1, 0, 1), None) == binding.PALSGD_EINVAL
+    assert lib().palsgd_set_tuning(ctx, 1000, 0) == binding.PALSGD_EINVAL
+    assert lib().palsgd_set_tuning(ctx, 4096, 3) == binding.PALSGD_EINVAL
+    assert lib().palsgd_set_tuning(ctx, 4096, 2) == 0
+    assert lib().palsgd_get_state(ctx, got, C.byref(n)) == 0 and list(got) == [5, 6, 7]    # state untouched
+    # nothing to do is not an error and launches nothing: every worker mixes, inner_step skips all
+    assert lib().palsgd_inner_step(ctx, 0, 1e-3, None, (C.c_uint8 * 3)(1, 1, 1), None) == 0
+    lib().palsgd_destroy(ctx)
+    for fn, args in ((lib().palsgd_step, (None, 0, 1e-3, 1.0, None, None, None)),
+                     (lib().palsgd_outer_step, (None, 0, None)), (lib().palsgd_draw, (None, 0, None))):
+        assert fn(*args) == binding.PALSGD_EINVAL
+    lib().palsgd_destroy(None)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libpalsgd.so")
+    with pytest.raises(ImportError):
+        binding.lib()
