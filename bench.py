@@ -126,7 +126,7 @@ def run_gpu(w, steps, warmup, chunk, outer_variant):
     return res
 
 
-def run_cpu_baseline(w, slice_div=8):
+def run_cpu_baseline(w, slice_div=2):
     """The oracle, as it stands, on the first 1/slice_div of every replica row for H+1 steps."""
     import oracle
     from paper_2504_18454_amd.workloads import flat_layout, to_bf16_bits
