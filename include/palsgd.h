@@ -20,8 +20,9 @@
  * Every base pointer must be 16-byte aligned.
  *
  * Ownership: the library borrows the buffer pointers from palsgd_init until
- * palsgd_destroy and owns only its context and a small device-side table (allocated
- * by the first call that launches a local update, 16 bytes per chunk of a row).
+ * palsgd_destroy and owns only its context and a device-side table of weight-decay
+ * values, 4 bytes per 64 elements of a row, made by the first gradient step and only
+ * when tensor_wd_mult is not uniform.
  * Streams: `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
  * device work is enqueued on it; calls return without waiting.
  * Errors: every entry point returns a palsgd_status and never aborts; argument
@@ -142,11 +143,15 @@ const char *palsgd_last_error(const palsgd_ctx *ctx);
  * must have synchronised work that still uses the table).  NULL is accepted. */
 void palsgd_destroy(palsgd_ctx *ctx);
 
-/* Launch-shape knobs for tuning and tests: elements per workgroup chunk (multiple of
- * 2048, <= 65536; 0 = default) and outer-kernel variant (0 = default choice,
- * 1 = per-lane walk over k, 2 = replicas split over the workgroup's waves with partial
- * sums staged through LDS).  EINVAL on other values. */
-palsgd_status palsgd_set_tuning(palsgd_ctx *ctx, uint32_t chunk_elems, uint32_t outer_variant);
+/* Launch-shape knobs for tuning and tests.  The kernels are throttled to a number of
+ * resident wavefronts per compute unit (fewer than the hardware allows streams better);
+ * step_waves_per_cu / outer_waves_per_cu override the built-in choice (0 = built-in,
+ * else 3..32; 32 = no throttle).  outer_variant: 0 = default choice, 1 = per-lane walk
+ * over k, 2 = replicas split over the workgroup's wavefronts with partial sums staged
+ * through LDS.  Results do not depend on the wave caps; the two outer variants differ in
+ * the order of the K-sum only.  EINVAL on other values. */
+palsgd_status palsgd_set_tuning(palsgd_ctx *ctx, uint32_t step_waves_per_cu, uint32_t outer_waves_per_cu,
+                                uint32_t outer_variant);
 
 #ifdef __cplusplus
 }

@@ -84,7 +84,7 @@ def lib() -> C.CDLL:
         L.palsgd_destroy.restype = None
         L.palsgd_destroy.argtypes = [vp]
         L.palsgd_set_tuning.restype = st
-        L.palsgd_set_tuning.argtypes = [vp, u32, u32]
+        L.palsgd_set_tuning.argtypes = [vp, u32, u32, u32]
         _lib = L
     return _lib
 
@@ -202,8 +202,9 @@ class Palsgd:
         arr = (C.c_uint64 * self.K)(*[int(v) for v in tau])
         _check(lib().palsgd_set_state(self._ctx, arr, int(n_outer)), self._ctx)
 
-    def palsgd_set_tuning(self, chunk_elems=0, outer_variant=0):
-        _check(lib().palsgd_set_tuning(self._ctx, int(chunk_elems), int(outer_variant)), self._ctx)
+    def palsgd_set_tuning(self, step_waves_per_cu=0, outer_waves_per_cu=0, outer_variant=0):
+        _check(lib().palsgd_set_tuning(self._ctx, int(step_waves_per_cu), int(outer_waves_per_cu),
+                                       int(outer_variant)), self._ctx)
 
     def palsgd_destroy(self):
         if self._ctx is not None and self._ctx.value:

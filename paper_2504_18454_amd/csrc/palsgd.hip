@@ -1,22 +1,31 @@
 // PALSGD parameter-update path for MI355X (gfx950, CDNA4): HIP kernels and the C ABI
 // declared in include/palsgd.h.
 //
-// Three kernels, all bound by HBM bandwidth (about one flop per byte moved, far below
-// the vector-ALU ridge), so the design rules are: every access a full-width coalesced
-// vector load/store (each wavefront instruction touches one contiguous 1 KiB / 512 B
-// span), every byte of state read once and written once per step, many independent
-// loads in flight per lane, one launch per step whatever the number of tensors.
+// Three kernels, all bound by HBM bandwidth (about one flop per byte moved; the IEEE
+// divide and square root cost nothing measurable), so the design rules are:
+//   * every access a full-width coalesced vector load/store: one wavefront instruction
+//     touches one contiguous 1 KiB span (512 B for bf16 gradients);
+//   * every byte of state read once and written once per step, non-temporal both ways;
+//   * one launch per step whatever the number of tensors: rows are flat, a per-64-element
+//     table carries the weight-decay multiplier only when tensors differ in it;
+//   * ONE wavefront per workgroup, one 16-byte group per lane and stream, no loop: the
+//     dispatcher streams tiles through the chip in address order, which keeps the DRAM
+//     pages of the 7 streams open;
+//   * a cap on the wavefronts resident per CU (through the workgroup's LDS allocation, of
+//     which nothing is used): about 72 KiB of loads+stores in flight per CU is the
+//     measured optimum; full occupancy loses 10-15 % to DRAM page conflicts.
 //
-//   step_kernel   Alg. 1 local update of all K workers in one launch: a workgroup
-//                 owns (chunk, worker); the worker's branch (gradient step / mixing
-//                 step) is uniform over the workgroup, so there is no divergence.
+//   step_kernel   Alg. 1 local update of all K workers in one launch: a wavefront owns
+//                 (tile of a row, worker); the worker's branch (gradient step / mixing
+//                 step) is uniform over the wavefront, so there is no divergence.
 //   outer_kernel  Alg. 1 outer step: K-way mean over the replica rows, Delta,
 //                 OuterOPT with (Nesterov) momentum, restart of the K workers.
 //   init_kernel   x_k^(0) <- x^(0), cleared optimizer state.
 //
-// No matrix cores: nothing here is a contraction.  No LDS in the step kernel: there is
-// no reuse to stage.  Each XCD's private L2 is irrelevant to pure streaming, so the
-// blockIdx -> (chunk, worker) map is a plain row-major one.
+// No matrix cores: nothing here is a contraction.  No data goes through LDS in the step
+// kernel: there is no reuse to stage.  Each XCD's private L2 is irrelevant to pure
+// streaming; remapping tiles so that an XCD walks a contiguous range measured slower
+// than the plain blockIdx order, so the map is the plain row-major one.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -34,17 +43,11 @@ namespace {
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;          // 4 wavefronts of 64 lanes
-constexpr int kGroup = kThreads * 4;   // elements one workgroup instruction covers
-constexpr uint32_t kDefaultChunk = 8192;
-constexpr uint32_t kMaxChunk = 65536;
-
-// One entry per contiguous range of a row that shares a weight-decay multiplier.
-struct Chunk {
-    uint64_t off;   // first element (multiple of 64)
-    uint32_t len;   // elements (multiple of 64, <= chunk size)
-    float wd;       // weight_decay * multiplier of the tensors inside
-};
+constexpr int kWave = 64;            // lanes of a wavefront = threads of a streaming workgroup
+constexpr int kTile = kWave * 4;     // elements a wavefront covers with one 16-byte group per lane
+constexpr int kThreads = 256;        // workgroup of the LDS-staged outer variant and of init
+constexpr uint32_t kLdsPerCU = 160u * 1024u;
+constexpr uint32_t kInflightDefault = 72u * 1024u;  // bytes of loads+stores in flight per CU
 
 // Per-launch, per-slot scalars; slot s of the grid's y dimension works on row `replica`.
 struct Slot {
@@ -62,6 +65,7 @@ struct StepArgs {
 
 struct Hyper {
     float beta1, beta2, eps, momentum;
+    float wd;        // weight decay when every tensor has the same multiplier
 };
 
 __device__ __forceinline__ f4 ld4(const float* p) { return __builtin_nontemporal_load((const f4*)p); }
@@ -122,103 +126,57 @@ __device__ __forceinline__ void sgdm4(f4& x, f4& b, f4 g, float mu, float lr, fl
     }
 }
 
-// Local update of step t for every (chunk, slot).  U = independent 4-element groups a
-// lane keeps in flight per loop trip.
-template <int INNER, int GDT, int U>
-__global__ __launch_bounds__(kThreads) void step_kernel(const StepArgs args, const Chunk* __restrict__ chunks,
-                                                        float* __restrict__ X, float* __restrict__ M,
-                                                        float* __restrict__ V, const void* __restrict__ G,
-                                                        const float* __restrict__ XG, uint64_t row_stride,
-                                                        Hyper h) {
+// Local update of step t.  Grid: x = tile of the row, y = slot.  A gradient-step wavefront
+// takes one tile (256 elements: 6.5-7 KiB of traffic); a mixing wavefront takes two (6 KiB),
+// so that both kinds keep about the same number of bytes in flight.
+// TAB: weight decay comes from a table with one entry per 64 elements of a row.
+template <int INNER, int GDT, bool TAB>
+__global__ __launch_bounds__(kWave) void step_kernel(const StepArgs args, const float* __restrict__ wd_tab,
+                                                     float* __restrict__ X, float* __restrict__ M,
+                                                     float* __restrict__ V, const void* __restrict__ G,
+                                                     const float* __restrict__ XG, uint64_t n, uint64_t row_stride,
+                                                     Hyper h) {
     const Slot sl = args.s[blockIdx.y];
-    const Chunk ch = chunks[blockIdx.x];
     const uint64_t row = (uint64_t)sl.replica * row_stride;
-    const uint32_t len = ch.len;
-    float* __restrict__ x = X + row + ch.off;
-    const uint32_t lane0 = threadIdx.x * 4;
+    const uint32_t lane4 = threadIdx.x * 4;
 
     if (sl.mix) {
         // pseudo-synchronization step: x_k <- x_k - beta (x_k - x)     (Sec. 4.1, second equation)
-        const float* __restrict__ xg = XG + ch.off;
-        const float beta = sl.beta_mix;
-        for (uint32_t base = 0; base < len; base += kGroup * U) {
-            f4 xv[U], gv[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t e = base + u * kGroup + lane0;
-                if (e < len) {
-                    xv[u] = ld4(x + e);
-                    gv[u] = ld4_cached(xg + e);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t e = base + u * kGroup + lane0;
-                if (e < len) {
-                    f4 r = xv[u] - beta * (xv[u] - gv[u]);
-                    st4(x + e, r);
-                }
-            }
+        const uint64_t e0 = (uint64_t)blockIdx.x * (2 * kTile) + lane4;
+        if (e0 >= n) return;
+        const uint64_t e1 = e0 + kTile;
+        const bool two = e1 < n;
+        float* __restrict__ x = X + row;
+        f4 x0 = ld4(x + e0), g0 = ld4_cached(XG + e0), x1, g1;
+        if (two) {
+            x1 = ld4(x + e1);
+            g1 = ld4_cached(XG + e1);
         }
+        st4(x + e0, x0 - sl.beta_mix * (x0 - g0));
+        if (two) st4(x + e1, x1 - sl.beta_mix * (x1 - g1));
         return;
     }
 
     // gradient step: x_k <- InnerOPT(x_k, g_k, alpha/(1-p))             (Sec. 4.1, first equation)
-    float* __restrict__ m = M + row + ch.off;
-    const uint64_t gbase = row + ch.off;
+    const uint64_t e = (uint64_t)blockIdx.x * kTile + lane4;
+    if (e >= n) return;
+    const uint64_t o = row + e;
     typedef GradLoad<GDT> GL;
+    typename GL::raw gr = GL::load(G, o);
+    f4 xv = ld4(X + o), mv = ld4(M + o);
+    const float wd = TAB ? wd_tab[e >> 6] : h.wd;
     if (INNER == PALSGD_INNER_ADAMW) {
-        float* __restrict__ v = V + row + ch.off;
-        const float decay = sl.lr * ch.wd;
-        for (uint32_t base = 0; base < len; base += kGroup * U) {
-            f4 xv[U], mv[U], vv[U];
-            typename GL::raw gr[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t e = base + u * kGroup + lane0;
-                if (e < len) {
-                    gr[u] = GL::load(G, gbase + e);
-                    xv[u] = ld4(x + e);
-                    mv[u] = ld4(m + e);
-                    vv[u] = ld4(v + e);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t e = base + u * kGroup + lane0;
-                if (e < len) {
-                    f4 g = GL::widen(gr[u]) * sl.gscale;
-                    adamw4(xv[u], mv[u], vv[u], g, h, sl.c1, sl.c2, decay);
-                    st4(x + e, xv[u]);
-                    st4(m + e, mv[u]);
-                    st4(v + e, vv[u]);
-                }
-            }
-        }
+        f4 vv = ld4(V + o);
+        f4 g = GL::widen(gr) * sl.gscale;
+        adamw4(xv, mv, vv, g, h, sl.c1, sl.c2, sl.lr * wd);
+        st4(X + o, xv);
+        st4(M + o, mv);
+        st4(V + o, vv);
     } else {
-        for (uint32_t base = 0; base < len; base += kGroup * U) {
-            f4 xv[U], mv[U];
-            typename GL::raw gr[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t e = base + u * kGroup + lane0;
-                if (e < len) {
-                    gr[u] = GL::load(G, gbase + e);
-                    xv[u] = ld4(x + e);
-                    mv[u] = ld4(m + e);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t e = base + u * kGroup + lane0;
-                if (e < len) {
-                    f4 g = GL::widen(gr[u]) * sl.gscale;
-                    sgdm4(xv[u], mv[u], g, h.momentum, sl.lr, ch.wd);
-                    st4(x + e, xv[u]);
-                    st4(m + e, mv[u]);
-                }
-            }
-        }
+        f4 g = GL::widen(gr) * sl.gscale;
+        sgdm4(xv, mv, g, h.momentum, sl.lr, wd);
+        st4(X + o, xv);
+        st4(M + o, mv);
     }
 }
 
@@ -235,14 +193,13 @@ __device__ __forceinline__ f4 outer4(f4 sum, f4 xg, f4& om, const OuterArgs& a) 
     return xg - a.lr * dir;
 }
 
-// Variant 1: each lane owns four consecutive elements and walks the K rows in ascending
-// order, eight independent loads in flight at a time.
-__global__ __launch_bounds__(kThreads) void outer_kernel_walk(float* __restrict__ X, float* __restrict__ XG,
-                                                              float* __restrict__ OM, uint64_t n4,
-                                                              uint64_t row_stride, uint32_t K, OuterArgs a) {
-    uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n4) return;
-    uint64_t e = i * 4;
+// Variant 1: one wavefront per tile; each lane owns four consecutive elements and walks the
+// K rows in ascending order, eight independent loads in flight at a time.
+__global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X, float* __restrict__ XG,
+                                                           float* __restrict__ OM, uint64_t n,
+                                                           uint64_t row_stride, uint32_t K, OuterArgs a) {
+    const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
+    if (e >= n) return;
     f4 xg = ld4(XG + e);
     f4 om = ld4(OM + e);
     f4 sum = {0.f, 0.f, 0.f, 0.f};
@@ -350,10 +307,12 @@ struct palsgd_ctx {
     std::vector<float> wd_mult;
     uint64_t P_padded = 0;
     uint32_t draw_threshold = 0;
-    uint32_t chunk_elems = kDefaultChunk;
+    bool wd_uniform = true;        // every tensor has the same weight-decay multiplier
+    float wd_eff0 = 0.0f;          // weight_decay * that multiplier
+    float* d_wd_tab = nullptr;     // else: weight_decay * multiplier per 64 elements of a row
+    uint32_t step_waves = 0;       // cap on resident wavefronts per CU, 0 = derive from bytes per wavefront
+    uint32_t outer_waves = 0;
     uint32_t outer_variant = 0;
-    Chunk* d_chunks = nullptr;
-    uint32_t n_chunks = 0;
     uint64_t tau[PALSGD_MAX_K] = {0};
     uint64_t n_outer = 0;
     uint64_t last_outer_t = 0;
@@ -381,40 +340,47 @@ palsgd_status layout_impl(uint32_t n_tensors, const uint64_t* numel, uint64_t* P
     return PALSGD_OK;
 }
 
-// Cut the row into chunks: neighbouring tensors with the same multiplier form one range
-// (rows are flat, padding included), each range is cut every chunk_elems elements.
-palsgd_status build_chunks(palsgd_ctx* c) {
-    std::vector<Chunk> host;
+// Device table with weight_decay * multiplier for every 64 elements of a row (a tensor's
+// tail padding takes the tensor's value).  Only needed when the multipliers differ.
+palsgd_status build_wd_table(palsgd_ctx* c) {
+    const uint64_t blocks = c->P_padded / 64;
+    std::vector<float> host(blocks);
     const size_t nt = c->numel.size();
-    size_t j = 0;
-    while (j < nt) {
-        size_t j2 = j + 1;
-        while (j2 < nt && c->wd_mult[j2] == c->wd_mult[j]) ++j2;
-        uint64_t begin = c->offset[j];
-        uint64_t end = j2 < nt ? c->offset[j2] : c->P_padded;
+    for (size_t j = 0; j < nt; ++j) {
+        uint64_t begin = c->offset[j] / 64;
+        uint64_t end = (j + 1 < nt ? c->offset[j + 1] : c->P_padded) / 64;
         float wd = (float)((double)c->cfg.weight_decay * (double)c->wd_mult[j]);
-        for (uint64_t o = begin; o < end; o += c->chunk_elems) {
-            uint64_t l = end - o < c->chunk_elems ? end - o : c->chunk_elems;
-            host.push_back(Chunk{o, (uint32_t)l, wd});
-        }
-        j = j2;
+        for (uint64_t q = begin; q < end; ++q) host[q] = wd;
     }
-    Chunk* d = nullptr;
-    hipError_t e = hipMalloc(&d, host.size() * sizeof(Chunk));
+    float* d = nullptr;
+    hipError_t e = hipMalloc(&d, blocks * sizeof(float));
     if (e != hipSuccess) {
-        set_error(c->error, "hipMalloc(chunk table): %s", hipGetErrorString(e));
+        set_error(c->error, "hipMalloc(weight-decay table): %s", hipGetErrorString(e));
         return PALSGD_ENOMEM;
     }
-    e = hipMemcpy(d, host.data(), host.size() * sizeof(Chunk), hipMemcpyHostToDevice);
+    e = hipMemcpy(d, host.data(), blocks * sizeof(float), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
-        set_error(c->error, "hipMemcpy(chunk table): %s", hipGetErrorString(e));
+        set_error(c->error, "hipMemcpy(weight-decay table): %s", hipGetErrorString(e));
         (void)hipFree(d);
         return PALSGD_EHIP;
     }
-    if (c->d_chunks) (void)hipFree(c->d_chunks);
-    c->d_chunks = d;
-    c->n_chunks = (uint32_t)host.size();
+    c->d_wd_tab = d;
     return PALSGD_OK;
+}
+
+// LDS bytes to request per workgroup so that at most `groups` workgroups are resident on a
+// CU (0 = no cap).  The kernels use none of it: the allocation is the occupancy throttle.
+uint32_t lds_cap(uint32_t groups, uint32_t static_lds) {
+    if (groups == 0 || groups >= 32) return 0;
+    uint32_t l = kLdsPerCU / groups / 512u * 512u;
+    if (l > 65536u) l = 65536u;
+    return l > static_lds ? l - static_lds : 0;
+}
+
+// Wavefronts per CU that keep about kInflightDefault bytes of loads+stores in flight.
+uint32_t auto_waves(uint32_t bytes_per_wave) {
+    uint32_t w = (kInflightDefault + bytes_per_wave / 2) / bytes_per_wave;
+    return w < 3 ? 3 : (w > 32 ? 32 : w);
 }
 
 palsgd_status check_launch(palsgd_ctx* c, const char* what) {
@@ -427,11 +393,21 @@ palsgd_status check_launch(palsgd_ctx* c, const char* what) {
 }
 
 template <int INNER, int GDT>
-void launch_step(palsgd_ctx* c, const StepArgs& args, uint32_t n_slots, hipStream_t st) {
-    dim3 grid(c->n_chunks, n_slots), block(kThreads);
-    Hyper h{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum};
-    step_kernel<INNER, GDT, 2><<<grid, block, 0, st>>>(args, c->d_chunks, c->buf.X, c->buf.M, c->buf.V, c->buf.G,
-                                                       c->buf.XG, c->buf.row_stride, h);
+void launch_step(palsgd_ctx* c, const StepArgs& args, uint32_t n_slots, bool any_grad, hipStream_t st) {
+    const uint64_t n = c->P_padded;
+    // mixing wavefronts take two tiles each, so a mixing-only launch needs half the grid
+    const uint32_t tiles = (uint32_t)(any_grad ? (n + kTile - 1) / kTile : (n + 2 * kTile - 1) / (2 * kTile));
+    const uint32_t per_elem = any_grad ? (INNER == PALSGD_INNER_ADAMW ? 24u : 16u) + (GDT == PALSGD_GRAD_F32 ? 4u : 2u)
+                                       : 24u;
+    const uint32_t waves = c->step_waves ? c->step_waves : auto_waves(per_elem * kTile);
+    dim3 grid(tiles, n_slots), block(kWave);
+    Hyper h{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum, c->wd_eff0};
+    if (c->wd_uniform)
+        step_kernel<INNER, GDT, false><<<grid, block, lds_cap(waves, 0), st>>>(
+            args, nullptr, c->buf.X, c->buf.M, c->buf.V, c->buf.G, c->buf.XG, n, c->buf.row_stride, h);
+    else
+        step_kernel<INNER, GDT, true><<<grid, block, lds_cap(waves, 0), st>>>(
+            args, c->d_wd_tab, c->buf.X, c->buf.M, c->buf.V, c->buf.G, c->buf.XG, n, c->buf.row_stride, h);
 }
 
 // Shared body of palsgd_inner_step / palsgd_pseudo_sync / palsgd_step.
@@ -488,16 +464,18 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
         }
     }
     if (n == 0) return PALSGD_OK;
-    if (!c->d_chunks) {  // the device table is made on the first launch that needs it
-        palsgd_status rc = build_chunks(c);
+    bool any_grad = false;
+    for (uint32_t k = 0; k < K; ++k) any_grad = any_grad || stepped[k];
+    if (any_grad && !c->wd_uniform && !c->d_wd_tab) {  // made by the first launch that needs it
+        palsgd_status rc = build_wd_table(c);
         if (rc != PALSGD_OK) return rc;
     }
     hipStream_t st = (hipStream_t)stream;
     const bool adamw = c->cfg.inner == PALSGD_INNER_ADAMW, bf16 = c->cfg.grad_dtype == PALSGD_GRAD_BF16;
-    if (adamw && bf16) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16>(c, args, n, st);
-    else if (adamw) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_F32>(c, args, n, st);
-    else if (bf16) launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_BF16>(c, args, n, st);
-    else launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_F32>(c, args, n, st);
+    if (adamw && bf16) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16>(c, args, n, any_grad, st);
+    else if (adamw) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_F32>(c, args, n, any_grad, st);
+    else if (bf16) launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_BF16>(c, args, n, any_grad, st);
+    else launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_F32>(c, args, n, any_grad, st);
     palsgd_status rc = check_launch(c, who);
     if (rc != PALSGD_OK) return rc;
     for (uint32_t k = 0; k < K; ++k)
@@ -577,6 +555,8 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
     c->cfg.tensor_numel = nullptr;  // the caller's arrays are not kept
     c->cfg.tensor_wd_mult = nullptr;
     c->P_padded = P_padded;
+    for (float m : c->wd_mult) c->wd_uniform = c->wd_uniform && m == c->wd_mult[0];
+    c->wd_eff0 = (float)((double)cfg->weight_decay * (double)c->wd_mult[0]);
     c->draw_threshold = (uint32_t)std::floor(cfg->p * 16777216.0);
     if (x0_dev) {
         uint64_t n4 = P_padded / 4;
@@ -626,15 +606,20 @@ palsgd_status palsgd_outer_step(palsgd_ctx* ctx, uint64_t t, void* stream) {
     }
     const uint32_t K = ctx->cfg.K;
     OuterArgs a{(float)(1.0 / (double)K), ctx->cfg.outer_lr, ctx->cfg.outer_momentum, ctx->cfg.outer_nesterov ? 1 : 0};
-    const uint64_t n4 = ctx->P_padded / 4;
+    const uint64_t n = ctx->P_padded;
     hipStream_t st = (hipStream_t)stream;
-    uint32_t variant = ctx->outer_variant ? ctx->outer_variant : 1u;
+    const uint32_t variant = ctx->outer_variant ? ctx->outer_variant : 1u;
+    const uint32_t waves = ctx->outer_waves ? ctx->outer_waves : auto_waves((8u * K + 16u) * kTile);
     if (variant == 2) {
+        const uint64_t n4 = n / 4;
         uint32_t blocks = (uint32_t)((n4 + 255) / 256);
-        outer_kernel_lds<<<blocks, kThreads, 0, st>>>(ctx->buf.X, ctx->buf.XG, ctx->buf.OM, n4, ctx->buf.row_stride, K, a);
+        uint32_t groups = waves / 4 ? waves / 4 : 1;  // a workgroup of this variant is four wavefronts
+        outer_kernel_lds<<<blocks, kThreads, lds_cap(groups, 16384), st>>>(ctx->buf.X, ctx->buf.XG, ctx->buf.OM, n4,
+                                                                           ctx->buf.row_stride, K, a);
     } else {
-        uint32_t blocks = (uint32_t)((n4 + kThreads - 1) / kThreads);
-        outer_kernel_walk<<<blocks, kThreads, 0, st>>>(ctx->buf.X, ctx->buf.XG, ctx->buf.OM, n4, ctx->buf.row_stride, K, a);
+        uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
+        outer_kernel_walk<<<tiles, kWave, lds_cap(waves, 0), st>>>(ctx->buf.X, ctx->buf.XG, ctx->buf.OM, n,
+                                                                   ctx->buf.row_stride, K, a);
     }
     palsgd_status rc = check_launch(ctx, "palsgd_outer_step");
     if (rc != PALSGD_OK) return rc;
@@ -667,28 +652,24 @@ const char* palsgd_last_error(const palsgd_ctx* ctx) { return ctx ? ctx->error :
 
 void palsgd_destroy(palsgd_ctx* ctx) {
     if (!ctx) return;
-    if (ctx->d_chunks) (void)hipFree(ctx->d_chunks);
+    if (ctx->d_wd_tab) (void)hipFree(ctx->d_wd_tab);
     delete ctx;
 }
 
-palsgd_status palsgd_set_tuning(palsgd_ctx* ctx, uint32_t chunk_elems, uint32_t outer_variant) {
+palsgd_status palsgd_set_tuning(palsgd_ctx* ctx, uint32_t step_waves_per_cu, uint32_t outer_waves_per_cu,
+                                uint32_t outer_variant) {
     if (!ctx) {
         set_error(g_error, "palsgd_set_tuning: NULL context");
         return PALSGD_EINVAL;
     }
-    if (chunk_elems == 0) chunk_elems = kDefaultChunk;
-    if (chunk_elems % 2048 != 0 || chunk_elems > kMaxChunk || outer_variant > 2) {
-        set_error(ctx->error, "palsgd_set_tuning: chunk_elems must be a multiple of 2048 <= 65536, outer_variant 0..2");
+    auto bad = [](uint32_t w) { return w != 0 && (w < 3 || w > 32); };
+    if (bad(step_waves_per_cu) || bad(outer_waves_per_cu) || outer_variant > 2) {
+        set_error(ctx->error, "palsgd_set_tuning: waves per CU must be 0 or 3..32, outer_variant 0..2");
         return PALSGD_EINVAL;
     }
+    ctx->step_waves = step_waves_per_cu;
+    ctx->outer_waves = outer_waves_per_cu;
     ctx->outer_variant = outer_variant;
-    if (chunk_elems != ctx->chunk_elems) {
-        ctx->chunk_elems = chunk_elems;
-        if (ctx->d_chunks) {  // hipFree waits for the device, so no launch still reads the old table
-            (void)hipFree(ctx->d_chunks);
-            ctx->d_chunks = nullptr;
-        }
-    }
     return PALSGD_OK;
 }
 

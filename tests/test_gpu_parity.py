@@ -58,11 +58,11 @@ def test_replica_counts(K):
     r.close()
 
 
-@pytest.mark.parametrize("variant,chunk", [(1, 2048), (2, 2048), (1, 65536), (2, 16384)])
-def test_tuning_shapes_agree_with_oracle(variant, chunk):
+@pytest.mark.parametrize("variant,step_waves,outer_waves", [(1, 3, 3), (2, 32, 4), (1, 0, 32), (2, 11, 0), (2, 5, 8)])
+def test_tuning_shapes_agree_with_oracle(variant, step_waves, outer_waves):
     r = _run(K=6, numels=[100000, 64, 777, 40000], inner="adamw", grad_dtype="bf16", p=0.2, H=3, seed=15,
              wd_mult=[1, 0, 0, 1], row_extra=1)
-    r.lib.palsgd_set_tuning(chunk, variant)
+    r.lib.palsgd_set_tuning(step_waves, outer_waves, variant)
     r.iterate(9)
     r.compare()
     r.close()
