@@ -35,6 +35,12 @@ def _load():
         _lib.ora_local_step.argtypes = [C.c_void_p, C.c_uint64, C.c_double, C.c_double,
                                         C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.ora_outer_step.argtypes = [C.c_void_p]
+        _lib.ora_ddp_step.argtypes = [C.c_void_p, C.c_double, C.c_void_p]
+        _lib.ora_grad_norm.restype = C.c_double
+        _lib.ora_grad_norm.argtypes = [C.c_void_p, C.c_int, C.c_uint64]
+        _lib.ora_clip_scale.restype = C.c_double
+        _lib.ora_clip_scale.argtypes = [C.c_double, C.c_double]
+        _lib.ora_diagnostics.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p]
         _lib.ora_iteration.restype = C.c_int
         _lib.ora_iteration.argtypes = [C.c_void_p, C.c_uint64, C.c_double, C.c_double,
                                        C.c_void_p, C.c_void_p, C.c_void_p]
@@ -93,6 +99,24 @@ def outer(X, xg, om, lr_o, mu_o, nesterov):
     K, row = X.shape
     _load().ora_outer(_ptr(X, np.float32), row, K, _ptr(xg, np.float32), _ptr(om, np.float32),
                       xg.size, float(lr_o), float(mu_o), int(bool(nesterov)))
+
+
+def grad_norm(g):
+    gp, gd = _gptr(g)
+    return float(_load().ora_grad_norm(gp, gd, g.size))
+
+
+def clip_scale(norm, max_norm):
+    return float(_load().ora_clip_scale(float(norm), float(max_norm)))
+
+
+def diagnostics(X, xg):
+    """-> (Xi, |Delta|^2) for X [K, row] and xg [n <= row]."""
+    K, row = X.shape
+    out = np.zeros(2, np.float64)
+    _load().ora_diagnostics(_ptr(X, np.float32), row, K, _ptr(xg, np.float32), xg.size,
+                            out.ctypes.data_as(C.c_void_p))
+    return float(out[0]), float(out[1])
 
 
 class _CState(C.Structure):
@@ -179,6 +203,16 @@ class OracleState:
 
     def outer_step(self):
         self.lib.ora_outer_step(C.byref(self.s))
+
+    def ddp_step(self, alpha_t, grad_scale=None):
+        gs, gsp = self._opt(grad_scale, np.float64)
+        self.lib.ora_ddp_step(C.byref(self.s), float(np.float32(alpha_t)), gsp)
+
+    def grad_norms(self):
+        return np.array([grad_norm(self.G[k]) for k in range(self.K)])
+
+    def diagnostics(self):
+        return diagnostics(self.X, self.XG)
 
     def iteration(self, t, alpha_t, eta_t, grad_scale=None, mask_override=None):
         gs, gsp = self._opt(grad_scale, np.float64)

@@ -42,6 +42,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 /* ------------------------------------------------------------------------- */
@@ -86,12 +87,15 @@ int ora_draw(uint64_t seed, uint64_t t, uint32_t k, uint32_t K, double p)
 
 /* ------------------------------------------------------------------------- */
 /* Gradient element as a double.  dtype 0: fp32; dtype 1: bf16 (upper 16 bits */
-/* of an fp32, widened exactly).                                              */
+/* of an fp32, widened exactly); dtype 2: fp64 (an averaged gradient that     */
+/* was never rounded, used by the DDP step).                                  */
 /* ------------------------------------------------------------------------- */
 static double grad_at(const void *g, int dtype, uint64_t i)
 {
     if (dtype == 0)
         return (double)((const float *)g)[i];
+    if (dtype == 2)
+        return ((const double *)g)[i];
     uint32_t bits = (uint32_t)((const uint16_t *)g)[i] << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
@@ -297,4 +301,100 @@ int ora_iteration(ora_state *s, uint64_t t, double alpha_t, double eta_t,
         return 1;
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* DDP step (Sec. 3.1: an All-Reduce of the gradient at every step before the */
+/* optimizer update, so that all workers apply the same update; Sec. 4.3 and  */
+/* Sec. 5.1: the warm-up phase that precedes PALSGD):                         */
+/*   gbar = (1/K) sum_k grad_scale_k g_k           (k ascending, never rounded)*/
+/*   x <- InnerOPT(x, gbar, alpha_t)               (no 1/(1-p) rescale: there  */
+/*                                                  is no mixing branch here)  */
+/*   every worker holds the result: x_k <- x, and every worker's InnerOPT      */
+/*   state is the common one.                                                  */
+/* Precondition (true from initialisation through the warm-up): all workers    */
+/* are identical; the common model is read from XG, the common InnerOPT state  */
+/* from worker 0.                                                              */
+/* ------------------------------------------------------------------------- */
+void ora_ddp_step(ora_state *s, double alpha_t, const double *grad_scale)
+{
+    const uint64_t n = s->n;
+    double *gbar = (double *)malloc(sizeof(double) * (n ? n : 1));
+    size_t gbytes = s->g_dtype == 0 ? 4 : 2;
+    for (uint64_t i = 0; i < n; ++i) {
+        double sum = 0.0;
+        for (uint32_t k = 0; k < s->K; ++k) {
+            const void *gk = (const char *)s->G + (uint64_t)k * s->row_stride * gbytes;
+            sum += (grad_scale ? grad_scale[k] : 1.0) * grad_at(gk, s->g_dtype, i);
+        }
+        gbar[i] = sum / (double)s->K;
+    }
+    s->tau[0] += 1;
+    for (uint32_t j = 0; j < s->n_tensors; ++j) {
+        uint64_t off = s->tensor_offset[j];
+        uint64_t len = s->tensor_numel[j];
+        double wd = s->weight_decay * (s->tensor_wd_mult ? (double)s->tensor_wd_mult[j] : 1.0);
+        if (s->inner == 0)
+            ora_adamw(s->XG + off, s->M + off, s->V + off, gbar + off, 2, len, alpha_t, s->beta1,
+                      s->beta2, s->eps, wd, s->tau[0], 1.0);
+        else
+            ora_sgdm(s->XG + off, s->M + off, gbar + off, 2, len, alpha_t, s->momentum, wd, 1.0);
+    }
+    for (uint32_t k = 0; k < s->K; ++k) {
+        memcpy(s->X + (uint64_t)k * s->row_stride, s->XG, sizeof(float) * n);
+        if (k > 0) {
+            s->tau[k] = s->tau[0];
+            memcpy(s->M + (uint64_t)k * s->row_stride, s->M, sizeof(float) * n);
+            if (s->inner == 0)
+                memcpy(s->V + (uint64_t)k * s->row_stride, s->V, sizeof(float) * n);
+        }
+    }
+    free(gbar);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gradient clipping (App. B: "AdamW ... with gradient clipping enabled"; no  */
+/* threshold or norm is printed).  Reading: clipping by the global L2 norm of */
+/* one worker's gradient, the common deep-learning convention:                */
+/*   norm_k = sqrt(sum_i g_k[i]^2)       scale_k = min(1, c / (norm_k + 1e-6)) */
+/* The scale is what the local update takes as grad_scale[k].                 */
+/* ------------------------------------------------------------------------- */
+double ora_grad_norm(const void *g, int g_dtype, uint64_t n)
+{
+    double sum = 0.0;
+    for (uint64_t i = 0; i < n; ++i) {
+        double gi = grad_at(g, g_dtype, i);
+        sum += gi * gi;
+    }
+    return sqrt(sum);
+}
+
+double ora_clip_scale(double norm, double max_norm)
+{
+    double c = max_norm / (norm + 1e-6);
+    return c < 1.0 ? c : 1.0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Diagnostics of the theory (App. A.3, the consensus-distance lemma):        */
+/*   Xi = (1/K) sum_k |x_k - x|^2   (zero right after a synchronisation)       */
+/*   |Delta|^2 with Delta = x - (1/K) sum_k x_k  (the outer gradient, Sec 4.2) */
+/* out[0] = Xi, out[1] = |Delta|^2.  Nothing is modified.                      */
+/* ------------------------------------------------------------------------- */
+void ora_diagnostics(const float *X, uint64_t row_stride, uint32_t K, const float *xg, uint64_t n,
+                     double *out)
+{
+    double xi = 0.0, d2 = 0.0;
+    for (uint64_t i = 0; i < n; ++i) {
+        double sum = 0.0;
+        for (uint32_t k = 0; k < K; ++k) {
+            double d = (double)X[(uint64_t)k * row_stride + i] - (double)xg[i];
+            xi += d * d;
+            sum += (double)X[(uint64_t)k * row_stride + i];
+        }
+        double delta = (double)xg[i] - sum / (double)K;
+        d2 += delta * delta;
+    }
+    out[0] = xi / (double)K;
+    out[1] = d2;
 }
