@@ -20,9 +20,9 @@
  * Every base pointer must be 16-byte aligned.
  *
  * Ownership: the library borrows the buffer pointers from palsgd_init until
- * palsgd_destroy and owns only its context and a device-side table of weight-decay
- * values, 4 bytes per 64 elements of a row, made by the first gradient step and only
- * when tensor_wd_mult is not uniform.
+ * palsgd_destroy and owns only its context, a device-side table of weight-decay
+ * values (4 bytes per 64 elements of a row, made by the first gradient step and only
+ * when tensor_wd_mult is not uniform) and the scratch of the scalar reductions.
  * Streams: `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
  * device work is enqueued on it; calls return without waiting.
  * Errors: every entry point returns a palsgd_status and never aborts; argument
@@ -129,6 +129,34 @@ palsgd_status palsgd_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, float eta_
  * all k (Sec. 2.1: workers restart from the global model).  The caller decides when
  * ((t+1) mod H == 0 in Alg. 1); t is recorded for diagnostics only. */
 palsgd_status palsgd_outer_step(palsgd_ctx *ctx, uint64_t t, void *stream);
+
+/* DDP step of the warm-up phase that precedes PALSGD (Sec. 3.1: an All-Reduce of the
+ * gradient at every step before the optimizer update; Sec. 4.3, Sec. 5.1):
+ * gbar = (1/K) sum_k grad_scale[k] G[k];  x <- InnerOPT(x, gbar, alpha_t) (no 1/(1-p)
+ * rescale: there is no mixing branch);  the result is stored to XG and to every row of X,
+ * the InnerOPT state to every row of M, V, and every worker's step count advances.
+ * Precondition: all workers are identical (true from palsgd_init through the warm-up);
+ * the common model is read from XG, the common InnerOPT state from worker 0.  ESTATE if
+ * the workers' step counts differ.  OM is not touched.  Clipping scales left by
+ * palsgd_clip_grad_norm are not consumed here. */
+palsgd_status palsgd_ddp_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, const float *grad_scale, void *stream);
+
+/* Gradient clipping by the global L2 norm of each worker's gradient (App. B: "gradient
+ * clipping enabled"; the paper prints no threshold): norm_k = |G[k]|_2 and
+ * scale_k = min(1, max_norm / (norm_k + 1e-6)) are computed on the device, without a host
+ * round trip.  The next palsgd_inner_step / palsgd_step of this context multiplies worker
+ * k's gradient by scale_k (on top of grad_scale[k]) and forgets the scales.
+ * norms_out_dev: device array of K floats that receives the norms, or NULL.
+ * The first call allocates the library's reduction scratch (about P_padded/512 floats);
+ * palsgd_clip_grad_norm and palsgd_diagnostics share it and must be issued on one stream.
+ * EINVAL unless max_norm is finite and > 0. */
+palsgd_status palsgd_clip_grad_norm(palsgd_ctx *ctx, float max_norm, float *norms_out_dev, void *stream);
+
+/* Diagnostics of the paper's analysis (App. A.3): out_dev[0] = consensus distance
+ * Xi = (1/K) sum_k |x_k - XG|^2 (zero right after an outer step), out_dev[1] = |Delta|^2
+ * with Delta = XG - (1/K) sum_k x_k, the outer gradient of Sec. 4.2.  out_dev: device
+ * array of 2 floats.  Nothing else is modified.  Sums are formed in a fixed order. */
+palsgd_status palsgd_diagnostics(palsgd_ctx *ctx, float *out_dev, void *stream);
 
 /* Host-side scalar state for checkpoint / resume: tau[k] = gradient steps worker k
  * has taken (drives AdamW's bias correction), n_outer = outer steps taken. */

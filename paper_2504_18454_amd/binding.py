@@ -24,7 +24,8 @@ MAX_K = 64
 
 EXPORTS = ("palsgd_layout", "palsgd_init", "palsgd_draw", "palsgd_inner_step", "palsgd_pseudo_sync",
            "palsgd_step", "palsgd_outer_step", "palsgd_get_state", "palsgd_set_state",
-           "palsgd_last_error", "palsgd_destroy", "palsgd_set_tuning")
+           "palsgd_last_error", "palsgd_destroy", "palsgd_set_tuning", "palsgd_ddp_step",
+           "palsgd_clip_grad_norm", "palsgd_diagnostics")
 
 
 class PalsgdError(RuntimeError):
@@ -75,6 +76,12 @@ def lib() -> C.CDLL:
         L.palsgd_step.argtypes = [vp, u64, f, f, C.POINTER(f), C.POINTER(C.c_uint8), vp]
         L.palsgd_outer_step.restype = st
         L.palsgd_outer_step.argtypes = [vp, u64, vp]
+        L.palsgd_ddp_step.restype = st
+        L.palsgd_ddp_step.argtypes = [vp, u64, f, C.POINTER(f), vp]
+        L.palsgd_clip_grad_norm.restype = st
+        L.palsgd_clip_grad_norm.argtypes = [vp, f, vp, vp]
+        L.palsgd_diagnostics.restype = st
+        L.palsgd_diagnostics.argtypes = [vp, vp, vp]
         L.palsgd_get_state.restype = st
         L.palsgd_get_state.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
         L.palsgd_set_state.restype = st
@@ -191,6 +198,20 @@ class Palsgd:
 
     def palsgd_outer_step(self, t, stream=None):
         _check(lib().palsgd_outer_step(self._ctx, int(t), _stream_handle(stream)), self._ctx)
+
+    def palsgd_ddp_step(self, t, alpha_t, grad_scale=None, stream=None):
+        gs, gsp = _f32(grad_scale)
+        _check(lib().palsgd_ddp_step(self._ctx, int(t), alpha_t, gsp, _stream_handle(stream)), self._ctx)
+
+    def palsgd_clip_grad_norm(self, max_norm, norms_out=None, stream=None):
+        """norms_out: torch CUDA float32 tensor of K elements (or a device address), or None."""
+        ptr = None if norms_out is None else (norms_out if isinstance(norms_out, int) else norms_out.data_ptr())
+        _check(lib().palsgd_clip_grad_norm(self._ctx, max_norm, ptr, _stream_handle(stream)), self._ctx)
+
+    def palsgd_diagnostics(self, out, stream=None):
+        """out: torch CUDA float32 tensor of 2 elements (or a device address): Xi, |Delta|^2."""
+        ptr = out if isinstance(out, int) else out.data_ptr()
+        _check(lib().palsgd_diagnostics(self._ctx, ptr, _stream_handle(stream)), self._ctx)
 
     def palsgd_get_state(self):
         tau = (C.c_uint64 * self.K)()

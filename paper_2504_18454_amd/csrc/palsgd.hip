@@ -134,8 +134,9 @@ template <int INNER, int GDT, bool TAB>
 __global__ __launch_bounds__(kWave) void step_kernel(const StepArgs args, const float* __restrict__ wd_tab,
                                                      float* __restrict__ X, float* __restrict__ M,
                                                      float* __restrict__ V, const void* __restrict__ G,
-                                                     const float* __restrict__ XG, uint64_t n, uint64_t row_stride,
-                                                     Hyper h) {
+                                                     const float* __restrict__ XG,
+                                                     const float* __restrict__ clip_scale, uint64_t n,
+                                                     uint64_t row_stride, Hyper h) {
     const Slot sl = args.s[blockIdx.y];
     const uint64_t row = (uint64_t)sl.replica * row_stride;
     const uint32_t lane4 = threadIdx.x * 4;
@@ -165,15 +166,17 @@ __global__ __launch_bounds__(kWave) void step_kernel(const StepArgs args, const 
     typename GL::raw gr = GL::load(G, o);
     f4 xv = ld4(X + o), mv = ld4(M + o);
     const float wd = TAB ? wd_tab[e >> 6] : h.wd;
+    // per-replica gradient multiplier: the caller's, times the clipping scale left on the device
+    const float gs = clip_scale ? sl.gscale * clip_scale[sl.replica] : sl.gscale;
     if (INNER == PALSGD_INNER_ADAMW) {
         f4 vv = ld4(V + o);
-        f4 g = GL::widen(gr) * sl.gscale;
+        f4 g = GL::widen(gr) * gs;
         adamw4(xv, mv, vv, g, h, sl.c1, sl.c2, sl.lr * wd);
         st4(X + o, xv);
         st4(M + o, mv);
         st4(V + o, vv);
     } else {
-        f4 g = GL::widen(gr) * sl.gscale;
+        f4 g = GL::widen(gr) * gs;
         sgdm4(xv, mv, g, h.momentum, sl.lr, wd);
         st4(X + o, xv);
         st4(M + o, mv);
@@ -185,9 +188,11 @@ struct OuterArgs {
     int nesterov;
 };
 
-// OuterOPT on four elements given the replica sum (Sec. 4.2; Sec. 4.3).
-__device__ __forceinline__ f4 outer4(f4 sum, f4 xg, f4& om, const OuterArgs& a) {
-    f4 delta = xg - sum * a.inv_k;                 // Delta = x - mean_k x_k
+// OuterOPT on four elements given dsum = sum_k (x - x_k) (Sec. 4.2; Sec. 4.3).  Summing the
+// differences instead of the models keeps Delta accurate to fp32 relative to its own size
+// and makes it exactly zero when the workers equal the global model.
+__device__ __forceinline__ f4 outer4(f4 dsum, f4 xg, f4& om, const OuterArgs& a) {
+    f4 delta = dsum * a.inv_k;                     // Delta = mean_k (x - x_k)
     om = a.mu * om + delta;
     f4 dir = a.nesterov ? delta + a.mu * om : om;
     return xg - a.lr * dir;
@@ -210,7 +215,7 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
             if (k0 + u < K) t[u] = ld4(X + (uint64_t)(k0 + u) * row_stride + e);
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            if (k0 + u < K) sum += t[u];
+            if (k0 + u < K) sum += xg - t[u];
     }
     f4 xn = outer4(sum, xg, om, a);
     st4(XG + e, xn);
@@ -228,9 +233,13 @@ __global__ __launch_bounds__(kThreads) void outer_kernel_lds(float* __restrict__
     __shared__ f4 part[4][4][64];  // [wave][sub-tile][lane], 16 KiB
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const uint64_t tile4 = (uint64_t)blockIdx.x * 256;  // first float4 of the tile
-    f4 acc[4];
+    f4 acc[4], xgt[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) acc[s] = (f4){0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < 4; ++s) {
+        acc[s] = (f4){0.f, 0.f, 0.f, 0.f};
+        uint64_t i = tile4 + s * 64 + lane;
+        xgt[s] = i < n4 ? ld4_cached(XG + i * 4) : (f4){0.f, 0.f, 0.f, 0.f};
+    }
     for (uint32_t k = w; k < K; k += 4) {
         const float* row = X + (uint64_t)k * row_stride;
         f4 t[4];
@@ -240,7 +249,7 @@ __global__ __launch_bounds__(kThreads) void outer_kernel_lds(float* __restrict__
             t[s] = i < n4 ? ld4(row + i * 4) : (f4){0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
-        for (int s = 0; s < 4; ++s) acc[s] += t[s];
+        for (int s = 0; s < 4; ++s) acc[s] += xgt[s] - t[s];
     }
 #pragma unroll
     for (int s = 0; s < 4; ++s) part[w][s][lane] = acc[s];
@@ -249,7 +258,7 @@ __global__ __launch_bounds__(kThreads) void outer_kernel_lds(float* __restrict__
     if (i < n4) {
         const uint64_t e = i * 4;
         f4 sum = ((part[0][w][lane] + part[1][w][lane]) + part[2][w][lane]) + part[3][w][lane];
-        f4 xg = ld4(XG + e);
+        f4 xg = w == 0 ? xgt[0] : (w == 1 ? xgt[1] : (w == 2 ? xgt[2] : xgt[3]));
         f4 om = ld4(OM + e);
         f4 xn = outer4(sum, xg, om, a);
         st4(XG + e, xn);
@@ -275,6 +284,164 @@ __global__ __launch_bounds__(kThreads) void init_kernel(const float* __restrict_
         st4(X + r, v);
         st4(M + r, z);
         if (V) st4(V + r, z);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// DDP step of the warm-up phase (Sec. 3.1: All-Reduce of the gradient, then the optimizer
+// update, identical on every worker; Sec. 4.3).  One wavefront per tile: weighted mean of the
+// K gradient rows (k ascending, eight loads in flight), InnerOPT on the common model (read
+// from XG) with the common state (read from replica 0), result stored to XG and all K rows.
+struct DdpArgs {
+    float w[PALSGD_MAX_K];  // grad_scale[k]
+    float inv_k, lr, c1, c2;
+};
+
+template <int INNER, int GDT, bool TAB>
+__global__ __launch_bounds__(kWave) void ddp_kernel(const DdpArgs a, const float* __restrict__ wd_tab,
+                                                    float* __restrict__ X, float* __restrict__ M,
+                                                    float* __restrict__ V, const void* __restrict__ G,
+                                                    float* __restrict__ XG, uint64_t n, uint64_t row_stride,
+                                                    uint32_t K, Hyper h) {
+    const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
+    if (e >= n) return;
+    typedef GradLoad<GDT> GL;
+    f4 xv = ld4(XG + e), mv = ld4(M + e), vv;
+    if (INNER == PALSGD_INNER_ADAMW) vv = ld4(V + e);
+    f4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t k0 = 0; k0 < K; k0 += 8) {
+        typename GL::raw t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (k0 + u < K) t[u] = GL::load(G, (uint64_t)(k0 + u) * row_stride + e);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (k0 + u < K) sum += GL::widen(t[u]) * a.w[k0 + u];
+    }
+    const f4 g = sum * a.inv_k;
+    const float wd = TAB ? wd_tab[e >> 6] : h.wd;
+    if (INNER == PALSGD_INNER_ADAMW)
+        adamw4(xv, mv, vv, g, h, a.c1, a.c2, a.lr * wd);
+    else
+        sgdm4(xv, mv, g, h.momentum, a.lr, wd);
+    st4(XG + e, xv);
+    for (uint32_t k = 0; k < K; ++k) {
+        const uint64_t o = (uint64_t)k * row_stride + e;
+        st4(X + o, xv);
+        st4(M + o, mv);
+        if (INNER == PALSGD_INNER_ADAMW) st4(V + o, vv);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Reductions to scalars: lane-local accumulation, a shuffle tree inside the wavefront, one
+// partial per wavefront in device scratch, and a second single-workgroup pass that adds the
+// partials in double in a fixed order (deterministic run to run).
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    return v;  // lane 0 holds the sum
+}
+
+constexpr int kNormTiles = 16;  // tiles a wavefront of the norm kernel walks: one partial per 4096 elements
+constexpr int kDiagTiles = 8;   // same for the diagnostics kernel: one partial pair per 2048 elements
+
+// Sum of squares of one replica's gradient row, per wavefront (App. B: gradient clipping).
+template <int GDT>
+__global__ __launch_bounds__(kWave) void sumsq_kernel(const void* __restrict__ G, float* __restrict__ partial,
+                                                      uint64_t n, uint64_t row_stride, uint32_t per_row) {
+    typedef GradLoad<GDT> GL;
+    const uint64_t base = (uint64_t)blockIdx.x * (kTile * kNormTiles) + threadIdx.x * 4;
+    const uint64_t row = (uint64_t)blockIdx.y * row_stride;
+    float acc = 0.f;
+#pragma unroll 4
+    for (int u = 0; u < kNormTiles; ++u) {
+        const uint64_t e = base + (uint64_t)u * kTile;
+        if (e < n) {
+            f4 g = GL::widen(GL::load(G, row + e));
+            acc += (g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w);
+        }
+    }
+    acc = wave_sum(acc);
+    if (threadIdx.x == 0) partial[(uint64_t)blockIdx.y * per_row + blockIdx.x] = acc;
+}
+
+// Fixed-order sum of `count` floats in double by one workgroup; every thread returns the total.
+__device__ double block_sum(const float* __restrict__ v, uint32_t count, double* lds) {
+    double acc = 0.0;
+    for (uint32_t j = threadIdx.x; j < count; j += kThreads) acc += (double)v[j];
+    lds[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = kThreads / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) lds[threadIdx.x] += lds[threadIdx.x + s];
+        __syncthreads();
+    }
+    double total = lds[0];
+    __syncthreads();
+    return total;
+}
+
+// norm_k = sqrt(sum of squares); scale_k = min(1, max_norm / (norm_k + 1e-6)).  One workgroup per replica.
+__global__ __launch_bounds__(kThreads) void clip_finish_kernel(const float* __restrict__ partial, uint32_t per_row,
+                                                               float max_norm, float* __restrict__ scale,
+                                                               float* __restrict__ norms_out) {
+    __shared__ double lds[kThreads];
+    const uint32_t k = blockIdx.x;
+    double total = block_sum(partial + (uint64_t)k * per_row, per_row, lds);
+    if (threadIdx.x == 0) {
+        double norm = sqrt(total);
+        double c = (double)max_norm / (norm + 1e-6);
+        scale[k] = (float)(c < 1.0 ? c : 1.0);
+        if (norms_out) norms_out[k] = (float)norm;
+    }
+}
+
+// Consensus distance and outer-gradient norm (App. A.3): per wavefront, partial sums of
+// sum_k |x_k - x|^2 and of |x - mean_k x_k|^2.
+__global__ __launch_bounds__(kWave) void diag_kernel(const float* __restrict__ X, const float* __restrict__ XG,
+                                                     float* __restrict__ partial, uint64_t n, uint64_t row_stride,
+                                                     uint32_t K, float inv_k, uint32_t n_part) {
+    const uint64_t base = (uint64_t)blockIdx.x * (kTile * kDiagTiles) + threadIdx.x * 4;
+    float xi = 0.f, d2 = 0.f;
+    for (int u = 0; u < kDiagTiles; ++u) {
+        const uint64_t e = base + (uint64_t)u * kTile;
+        if (e >= n) break;
+        const f4 xg = ld4_cached(XG + e);
+        f4 sum = {0.f, 0.f, 0.f, 0.f}, sq = {0.f, 0.f, 0.f, 0.f};
+        for (uint32_t k0 = 0; k0 < K; k0 += 8) {
+            f4 t[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (k0 + q < K) t[q] = ld4_cached(X + (uint64_t)(k0 + q) * row_stride + e);
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (k0 + q < K) {
+                    f4 d = xg - t[q];
+                    sq += d * d;
+                    sum += d;
+                }
+        }
+        const f4 delta = sum * inv_k;
+        const f4 dd = delta * delta;
+        xi += (sq.x + sq.y) + (sq.z + sq.w);
+        d2 += (dd.x + dd.y) + (dd.z + dd.w);
+    }
+    xi = wave_sum(xi);
+    d2 = wave_sum(d2);
+    if (threadIdx.x == 0) {
+        partial[blockIdx.x] = xi;
+        partial[n_part + blockIdx.x] = d2;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void diag_finish_kernel(const float* __restrict__ partial, uint32_t n_part,
+                                                               float inv_k, float* __restrict__ out) {
+    __shared__ double lds[kThreads];
+    double xi = block_sum(partial, n_part, lds);
+    double d2 = block_sum(partial + n_part, n_part, lds);
+    if (threadIdx.x == 0) {
+        out[0] = (float)(xi * (double)inv_k);
+        out[1] = (float)d2;
     }
 }
 
@@ -310,6 +477,9 @@ struct palsgd_ctx {
     bool wd_uniform = true;        // every tensor has the same weight-decay multiplier
     float wd_eff0 = 0.0f;          // weight_decay * that multiplier
     float* d_wd_tab = nullptr;     // else: weight_decay * multiplier per 64 elements of a row
+    float* d_scratch = nullptr;    // partial sums of the scalar reductions + their K+2 results
+    uint64_t scratch_floats = 0;
+    bool clip_armed = false;       // d_scratch holds clipping scales for the next gradient step
     uint32_t step_waves = 0;       // cap on resident wavefronts per CU, 0 = derive from bytes per wavefront
     uint32_t outer_waves = 0;
     uint32_t outer_variant = 0;
@@ -378,9 +548,9 @@ uint32_t lds_cap(uint32_t groups, uint32_t static_lds) {
 }
 
 // Wavefronts per CU that keep about kInflightDefault bytes of loads+stores in flight.
-uint32_t auto_waves(uint32_t bytes_per_wave) {
+uint32_t auto_waves(uint32_t bytes_per_wave, uint32_t floor_waves = 3) {
     uint32_t w = (kInflightDefault + bytes_per_wave / 2) / bytes_per_wave;
-    return w < 3 ? 3 : (w > 32 ? 32 : w);
+    return w < floor_waves ? floor_waves : (w > 32 ? 32 : w);
 }
 
 palsgd_status check_launch(palsgd_ctx* c, const char* what) {
@@ -392,8 +562,35 @@ palsgd_status check_launch(palsgd_ctx* c, const char* what) {
     return PALSGD_OK;
 }
 
+// Scratch layout: [0, K) clipping scales, [K, K+2) diagnostics staging, then the partial sums.
+uint32_t norm_parts(const palsgd_ctx* c) {
+    return (uint32_t)((c->P_padded + (uint64_t)kTile * kNormTiles - 1) / ((uint64_t)kTile * kNormTiles));
+}
+uint32_t diag_parts(const palsgd_ctx* c) {
+    return (uint32_t)((c->P_padded + (uint64_t)kTile * kDiagTiles - 1) / ((uint64_t)kTile * kDiagTiles));
+}
+float* clip_scales(palsgd_ctx* c) { return c->d_scratch; }
+float* scratch_partials(palsgd_ctx* c) { return c->d_scratch + PALSGD_MAX_K + 64; }
+
+palsgd_status ensure_scratch(palsgd_ctx* c) {
+    if (c->d_scratch) return PALSGD_OK;
+    uint64_t parts = (uint64_t)c->cfg.K * norm_parts(c);
+    if (parts < 2ull * diag_parts(c)) parts = 2ull * diag_parts(c);
+    uint64_t floats = PALSGD_MAX_K + 64 + parts;
+    float* d = nullptr;
+    hipError_t e = hipMalloc(&d, floats * sizeof(float));
+    if (e != hipSuccess) {
+        set_error(c->error, "hipMalloc(reduction scratch): %s", hipGetErrorString(e));
+        return PALSGD_ENOMEM;
+    }
+    c->d_scratch = d;
+    c->scratch_floats = floats;
+    return PALSGD_OK;
+}
+
 template <int INNER, int GDT>
-void launch_step(palsgd_ctx* c, const StepArgs& args, uint32_t n_slots, bool any_grad, hipStream_t st) {
+void launch_step(palsgd_ctx* c, const StepArgs& args, uint32_t n_slots, bool any_grad, const float* clip,
+                 hipStream_t st) {
     const uint64_t n = c->P_padded;
     // mixing wavefronts take two tiles each, so a mixing-only launch needs half the grid
     const uint32_t tiles = (uint32_t)(any_grad ? (n + kTile - 1) / kTile : (n + 2 * kTile - 1) / (2 * kTile));
@@ -404,10 +601,10 @@ void launch_step(palsgd_ctx* c, const StepArgs& args, uint32_t n_slots, bool any
     Hyper h{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum, c->wd_eff0};
     if (c->wd_uniform)
         step_kernel<INNER, GDT, false><<<grid, block, lds_cap(waves, 0), st>>>(
-            args, nullptr, c->buf.X, c->buf.M, c->buf.V, c->buf.G, c->buf.XG, n, c->buf.row_stride, h);
+            args, nullptr, c->buf.X, c->buf.M, c->buf.V, c->buf.G, c->buf.XG, clip, n, c->buf.row_stride, h);
     else
         step_kernel<INNER, GDT, true><<<grid, block, lds_cap(waves, 0), st>>>(
-            args, c->d_wd_tab, c->buf.X, c->buf.M, c->buf.V, c->buf.G, c->buf.XG, n, c->buf.row_stride, h);
+            args, c->d_wd_tab, c->buf.X, c->buf.M, c->buf.V, c->buf.G, c->buf.XG, clip, n, c->buf.row_stride, h);
 }
 
 // Shared body of palsgd_inner_step / palsgd_pseudo_sync / palsgd_step.
@@ -472,12 +669,15 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
     }
     hipStream_t st = (hipStream_t)stream;
     const bool adamw = c->cfg.inner == PALSGD_INNER_ADAMW, bf16 = c->cfg.grad_dtype == PALSGD_GRAD_BF16;
-    if (adamw && bf16) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16>(c, args, n, any_grad, st);
-    else if (adamw) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_F32>(c, args, n, any_grad, st);
-    else if (bf16) launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_BF16>(c, args, n, any_grad, st);
-    else launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_F32>(c, args, n, any_grad, st);
+    // clipping scales computed by palsgd_clip_grad_norm are consumed by the first gradient step after it
+    const float* clip = any_grad && c->clip_armed ? clip_scales(c) : nullptr;
+    if (adamw && bf16) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16>(c, args, n, any_grad, clip, st);
+    else if (adamw) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_F32>(c, args, n, any_grad, clip, st);
+    else if (bf16) launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_BF16>(c, args, n, any_grad, clip, st);
+    else launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_F32>(c, args, n, any_grad, clip, st);
     palsgd_status rc = check_launch(c, who);
     if (rc != PALSGD_OK) return rc;
+    if (clip) c->clip_armed = false;
     for (uint32_t k = 0; k < K; ++k)
         if (stepped[k]) c->tau[k] += 1;
     return PALSGD_OK;
@@ -609,7 +809,7 @@ palsgd_status palsgd_outer_step(palsgd_ctx* ctx, uint64_t t, void* stream) {
     const uint64_t n = ctx->P_padded;
     hipStream_t st = (hipStream_t)stream;
     const uint32_t variant = ctx->outer_variant ? ctx->outer_variant : 1u;
-    const uint32_t waves = ctx->outer_waves ? ctx->outer_waves : auto_waves((8u * K + 16u) * kTile);
+    const uint32_t waves = ctx->outer_waves ? ctx->outer_waves : auto_waves((8u * K + 16u) * kTile, 4);  // K rows are walked 8 at a time: 4 is best from K=16 up
     if (variant == 2) {
         const uint64_t n4 = n / 4;
         uint32_t blocks = (uint32_t)((n4 + 255) / 256);
@@ -626,6 +826,113 @@ palsgd_status palsgd_outer_step(palsgd_ctx* ctx, uint64_t t, void* stream) {
     ctx->n_outer += 1;
     ctx->last_outer_t = t;
     return PALSGD_OK;
+}
+
+palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const float* grad_scale, void* stream) {
+    (void)t;
+    if (!ctx) {
+        set_error(g_error, "palsgd_ddp_step: NULL context");
+        return PALSGD_EINVAL;
+    }
+    if (!(alpha_t >= 0.0f) || !std::isfinite(alpha_t)) {
+        set_error(ctx->error, "palsgd_ddp_step: alpha_t must be finite and >= 0");
+        return PALSGD_EINVAL;
+    }
+    const uint32_t K = ctx->cfg.K;
+    for (uint32_t k = 1; k < K; ++k)
+        if (ctx->tau[k] != ctx->tau[0]) {
+            set_error(ctx->error, "palsgd_ddp_step: workers have taken different numbers of gradient steps "
+                                  "(%llu vs %llu): the DDP step needs identical workers",
+                      (unsigned long long)ctx->tau[0], (unsigned long long)ctx->tau[k]);
+            return PALSGD_ESTATE;
+        }
+    DdpArgs a;
+    for (uint32_t k = 0; k < PALSGD_MAX_K; ++k) a.w[k] = 1.0f;
+    if (grad_scale)
+        for (uint32_t k = 0; k < K; ++k) {
+            if (!std::isfinite(grad_scale[k])) {
+                set_error(ctx->error, "palsgd_ddp_step: grad_scale[%u] is not finite", k);
+                return PALSGD_EINVAL;
+            }
+            a.w[k] = grad_scale[k];
+        }
+    const double tau = (double)(ctx->tau[0] + 1);
+    a.inv_k = (float)(1.0 / (double)K);
+    a.lr = alpha_t;  // DDP has no mixing branch, so no 1/(1-p) rescale
+    a.c1 = a.c2 = 0.0f;
+    const bool adamw = ctx->cfg.inner == PALSGD_INNER_ADAMW, bf16 = ctx->cfg.grad_dtype == PALSGD_GRAD_BF16;
+    if (adamw) {
+        a.c1 = (float)((double)alpha_t / (1.0 - std::pow((double)ctx->cfg.beta1, tau)));
+        a.c2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)ctx->cfg.beta2, tau)));
+    }
+    if (!ctx->wd_uniform && !ctx->d_wd_tab) {
+        palsgd_status rc = build_wd_table(ctx);
+        if (rc != PALSGD_OK) return rc;
+    }
+    const uint64_t n = ctx->P_padded;
+    const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
+    const uint32_t per_elem = (adamw ? 12u + 12u * K : 8u + 8u * K) + 4u + K * (bf16 ? 2u : 4u);
+    const uint32_t lds = lds_cap(ctx->outer_waves ? ctx->outer_waves : auto_waves(per_elem * kTile, 4), 0);
+    Hyper h{ctx->cfg.beta1, ctx->cfg.beta2, ctx->cfg.eps, ctx->cfg.momentum, ctx->wd_eff0};
+    hipStream_t st = (hipStream_t)stream;
+    const palsgd_buffers& b = ctx->buf;
+#define PALSGD_DDP(I, D)                                                                                           \
+    if (ctx->wd_uniform)                                                                                           \
+        ddp_kernel<I, D, false><<<tiles, kWave, lds, st>>>(a, nullptr, b.X, b.M, b.V, b.G, b.XG, n, b.row_stride, K, h); \
+    else                                                                                                           \
+        ddp_kernel<I, D, true><<<tiles, kWave, lds, st>>>(a, ctx->d_wd_tab, b.X, b.M, b.V, b.G, b.XG, n, b.row_stride, K, h);
+    if (adamw && bf16) { PALSGD_DDP(PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16) }
+    else if (adamw) { PALSGD_DDP(PALSGD_INNER_ADAMW, PALSGD_GRAD_F32) }
+    else if (bf16) { PALSGD_DDP(PALSGD_INNER_SGDM, PALSGD_GRAD_BF16) }
+    else { PALSGD_DDP(PALSGD_INNER_SGDM, PALSGD_GRAD_F32) }
+#undef PALSGD_DDP
+    palsgd_status rc = check_launch(ctx, "palsgd_ddp_step");
+    if (rc != PALSGD_OK) return rc;
+    for (uint32_t k = 0; k < K; ++k) ctx->tau[k] += 1;
+    return PALSGD_OK;
+}
+
+palsgd_status palsgd_clip_grad_norm(palsgd_ctx* ctx, float max_norm, float* norms_out_dev, void* stream) {
+    if (!ctx) {
+        set_error(g_error, "palsgd_clip_grad_norm: NULL context");
+        return PALSGD_EINVAL;
+    }
+    if (!(max_norm > 0.0f) || !std::isfinite(max_norm)) {
+        set_error(ctx->error, "palsgd_clip_grad_norm: max_norm must be finite and > 0");
+        return PALSGD_EINVAL;
+    }
+    palsgd_status rc = ensure_scratch(ctx);
+    if (rc != PALSGD_OK) return rc;
+    const uint32_t K = ctx->cfg.K, per_row = norm_parts(ctx);
+    hipStream_t st = (hipStream_t)stream;
+    dim3 grid(per_row, K);
+    if (ctx->cfg.grad_dtype == PALSGD_GRAD_BF16)
+        sumsq_kernel<PALSGD_GRAD_BF16><<<grid, kWave, 0, st>>>(ctx->buf.G, scratch_partials(ctx), ctx->P_padded,
+                                                               ctx->buf.row_stride, per_row);
+    else
+        sumsq_kernel<PALSGD_GRAD_F32><<<grid, kWave, 0, st>>>(ctx->buf.G, scratch_partials(ctx), ctx->P_padded,
+                                                              ctx->buf.row_stride, per_row);
+    clip_finish_kernel<<<K, kThreads, 0, st>>>(scratch_partials(ctx), per_row, max_norm, clip_scales(ctx), norms_out_dev);
+    rc = check_launch(ctx, "palsgd_clip_grad_norm");
+    if (rc != PALSGD_OK) return rc;
+    ctx->clip_armed = true;
+    return PALSGD_OK;
+}
+
+palsgd_status palsgd_diagnostics(palsgd_ctx* ctx, float* out_dev, void* stream) {
+    if (!ctx || !out_dev) {
+        set_error(ctx ? ctx->error : g_error, "palsgd_diagnostics: NULL argument");
+        return PALSGD_EINVAL;
+    }
+    palsgd_status rc = ensure_scratch(ctx);
+    if (rc != PALSGD_OK) return rc;
+    const uint32_t K = ctx->cfg.K, n_part = diag_parts(ctx);
+    const float inv_k = (float)(1.0 / (double)K);
+    hipStream_t st = (hipStream_t)stream;
+    diag_kernel<<<n_part, kWave, 0, st>>>(ctx->buf.X, ctx->buf.XG, scratch_partials(ctx), ctx->P_padded,
+                                          ctx->buf.row_stride, K, inv_k, n_part);
+    diag_finish_kernel<<<1, kThreads, 0, st>>>(scratch_partials(ctx), n_part, inv_k, out_dev);
+    return check_launch(ctx, "palsgd_diagnostics");
 }
 
 palsgd_status palsgd_get_state(const palsgd_ctx* ctx, uint64_t* tau, uint64_t* n_outer) {
@@ -653,6 +960,7 @@ const char* palsgd_last_error(const palsgd_ctx* ctx) { return ctx ? ctx->error :
 void palsgd_destroy(palsgd_ctx* ctx) {
     if (!ctx) return;
     if (ctx->d_wd_tab) (void)hipFree(ctx->d_wd_tab);
+    if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
     delete ctx;
 }
 

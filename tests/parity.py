@@ -128,12 +128,22 @@ class Run:
         for k in range(K):
             self.G[k].index_copy_(0, self.idx_dev, gd[k])
 
-    def iterate(self, steps, *, fused=True, grad_scale=None, mask_fn=None, check_every=0):
+    def iterate(self, steps, *, fused=True, grad_scale=None, mask_fn=None, check_every=0, clip=None):
         for _ in range(steps):
             t = self.t
             self.make_gradients()
             mo = None if mask_fn is None else np.asarray(mask_fn(t), np.uint8)
             gs64 = None if grad_scale is None else np.asarray(grad_scale, np.float32).astype(np.float64)
+            if clip is not None:
+                # global-norm clipping: a reduction over the whole row, so only for full-coverage runs
+                assert self.full
+                norms_dev = torch.empty(self.K, dtype=torch.float32, device=self.dev)
+                self.lib.palsgd_clip_grad_norm(clip, norms_dev)
+                norms = self.ora.grad_norms()
+                np.testing.assert_allclose(norms_dev.cpu().numpy(), norms, rtol=1e-5)
+                scales = np.array([oracle.clip_scale(v, float(np.float32(clip))) for v in norms])
+                gs64 = scales if gs64 is None else gs64 * scales
+                self.last_scales = scales
             mask_o, synced = self.ora.iteration(t, self.alpha, self.eta, grad_scale=gs64, mask_override=mo)
             if mo is None:
                 assert np.array_equal(self.lib.palsgd_draw(t), mask_o), f"draws differ at t={t}"
@@ -149,6 +159,27 @@ class Run:
             if check_every and self.t % check_every == 0:
                 self.compare()
         torch.cuda.synchronize()
+
+    def ddp_iterate(self, steps, grad_scale=None):
+        """DDP warm-up steps: every worker applies the update of the averaged gradient."""
+        gs64 = None if grad_scale is None else np.asarray(grad_scale, np.float32).astype(np.float64)
+        for _ in range(steps):
+            self.make_gradients()
+            self.ora.ddp_step(self.alpha, grad_scale=gs64)
+            self.lib.palsgd_ddp_step(self.t, self.alpha, grad_scale)
+            self.t += 1
+        torch.cuda.synchronize()
+
+    def compare_diagnostics(self, rtol=1e-5):
+        assert self.full
+        out = torch.empty(2, dtype=torch.float32, device=self.dev)
+        self.lib.palsgd_diagnostics(out)
+        got = out.cpu().numpy().astype(np.float64)
+        xi, d2 = self.ora.diagnostics()
+        # the device path sums its own fp32 state, the oracle its own: states agree to 1e-5 relative, and
+        # both quantities are sums of squares of differences of nearby numbers, so compare with slack
+        np.testing.assert_allclose(got, [xi, d2], rtol=max(rtol, 2e-3), atol=1e-12)
+        return got
 
     # ------------------------------------------------------------------ comparison
     def device_sample(self, T):
