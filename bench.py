@@ -59,7 +59,7 @@ def grad_bytes_per_elem(inner: str, grad_dtype: str) -> int:
     return (24 if inner == "adamw" else 16) + g          # read+write x,m(,v) + read g
 
 
-def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant):
+def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=False):
     import torch
 
     from paper_2504_18454_amd import Palsgd, make_config, palsgd_layout
@@ -152,6 +152,32 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant):
         blended_gbps=total_bytes / elapsed / 1e9,
     )
     torch.cuda.synchronize()
+    if extra:
+        # the kernels next to the hot path, each timed alone with events on the launch stream
+        def timed(fn, reps=10):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(reps):
+                fn()
+            b.record(stream)
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+        gB = 4 if w.grad_dtype == "f32" else 2
+        state = 12 if w.inner == "adamw" else 8
+        out2 = torch.empty(2, dtype=f, device=dev)
+        norms = torch.empty(K, dtype=f, device=dev)
+        ms = timed(lambda: ctx.palsgd_clip_grad_norm(1.0, norms, stream))
+        res["clip_grad_norm"] = dict(ms=ms, gbps=float(P) * K * gB / ms / 1e6, bytes_per_elem=K * gB)
+        ms = timed(lambda: ctx.palsgd_diagnostics(out2, stream))
+        res["diagnostics"] = dict(ms=ms, gbps=float(P) * (4 * K + 4) / ms / 1e6, bytes_per_elem=4 * K + 4)
+        ctx.palsgd_outer_step(0, stream)                # workers identical again, as the DDP step requires
+        tau0 = max(ctx.palsgd_get_state()[0])
+        ctx.palsgd_set_state([tau0] * K, ctx.palsgd_get_state()[1])
+        ddp_b = K * gB + state + 4 + K * state         # read K gradients + x, m(, v); write XG + K rows of x, m(, v)
+        ms = timed(lambda: ctx.palsgd_ddp_step(0, w.alpha, None, stream))
+        res["ddp_step"] = dict(ms=ms, gbps=float(P) * ddp_b / ms / 1e6, bytes_per_elem=ddp_b)
     ctx.palsgd_destroy()
     return res
 
@@ -195,6 +221,8 @@ def main():
     ap.add_argument("--outer-waves", type=int, default=0, help="resident wavefronts per CU, outer step (0 = library's choice)")
     ap.add_argument("--outer-variant", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extra-kernels", action="store_true",
+                    help="also time the DDP warm-up step, gradient-norm clipping and diagnostics kernels")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (K replicas share it); --gpus must be 1. "
@@ -202,7 +230,7 @@ def main():
         sys.exit(2)
     from paper_2504_18454_amd.workloads import workload
     w = workload(a.workload)
-    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant)
+    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels)
     cpu = None if a.no_cpu_baseline else run_cpu_baseline(w)
     gb = grad_bytes_per_elem(w.inner, w.grad_dtype)
     out = {
@@ -223,6 +251,8 @@ def main():
                          "bytes_per_elem": 8 * w.K + 16},
         "cpu_baseline": cpu,
     }
+    if a.extra_kernels:
+        out["extra_kernels"] = {k: r[k] for k in ("ddp_step", "clip_grad_norm", "diagnostics")}
     print(json.dumps(out))
 
 

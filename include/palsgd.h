@@ -130,6 +130,12 @@ palsgd_status palsgd_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, float eta_
  * ((t+1) mod H == 0 in Alg. 1); t is recorded for diagnostics only. */
 palsgd_status palsgd_outer_step(palsgd_ctx *ctx, uint64_t t, void *stream);
 
+/* palsgd_outer_step that also reports, at no extra memory traffic, the diagnostics of
+ * App. A.3 taken just before the update: diag_out_dev[0] = consensus distance
+ * Xi = (1/K) sum_k |x_k - XG|^2, diag_out_dev[1] = |Delta|^2 (device array of 2 floats;
+ * EINVAL if NULL).  Uses the library's reduction scratch (see palsgd_clip_grad_norm). */
+palsgd_status palsgd_outer_step_diag(palsgd_ctx *ctx, uint64_t t, float *diag_out_dev, void *stream);
+
 /* DDP step of the warm-up phase that precedes PALSGD (Sec. 3.1: an All-Reduce of the
  * gradient at every step before the optimizer update; Sec. 4.3, Sec. 5.1):
  * gbar = (1/K) sum_k grad_scale[k] G[k];  x <- InnerOPT(x, gbar, alpha_t) (no 1/(1-p)
@@ -147,8 +153,9 @@ palsgd_status palsgd_ddp_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, const 
  * round trip.  The next palsgd_inner_step / palsgd_step of this context multiplies worker
  * k's gradient by scale_k (on top of grad_scale[k]) and forgets the scales.
  * norms_out_dev: device array of K floats that receives the norms, or NULL.
- * The first call allocates the library's reduction scratch (about P_padded/512 floats);
- * palsgd_clip_grad_norm and palsgd_diagnostics share it and must be issued on one stream.
+ * The first call allocates the library's reduction scratch (about P_padded/128 floats);
+ * palsgd_clip_grad_norm, palsgd_diagnostics and palsgd_outer_step_diag share it and must
+ * be issued on one stream.
  * EINVAL unless max_norm is finite and > 0. */
 palsgd_status palsgd_clip_grad_norm(palsgd_ctx *ctx, float max_norm, float *norms_out_dev, void *stream);
 

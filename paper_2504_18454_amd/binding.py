@@ -25,7 +25,7 @@ MAX_K = 64
 EXPORTS = ("palsgd_layout", "palsgd_init", "palsgd_draw", "palsgd_inner_step", "palsgd_pseudo_sync",
            "palsgd_step", "palsgd_outer_step", "palsgd_get_state", "palsgd_set_state",
            "palsgd_last_error", "palsgd_destroy", "palsgd_set_tuning", "palsgd_ddp_step",
-           "palsgd_clip_grad_norm", "palsgd_diagnostics")
+           "palsgd_clip_grad_norm", "palsgd_diagnostics", "palsgd_outer_step_diag")
 
 
 class PalsgdError(RuntimeError):
@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
         L.palsgd_clip_grad_norm.argtypes = [vp, f, vp, vp]
         L.palsgd_diagnostics.restype = st
         L.palsgd_diagnostics.argtypes = [vp, vp, vp]
+        L.palsgd_outer_step_diag.restype = st
+        L.palsgd_outer_step_diag.argtypes = [vp, u64, vp, vp]
         L.palsgd_get_state.restype = st
         L.palsgd_get_state.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
         L.palsgd_set_state.restype = st
@@ -212,6 +214,11 @@ class Palsgd:
         """out: torch CUDA float32 tensor of 2 elements (or a device address): Xi, |Delta|^2."""
         ptr = out if isinstance(out, int) else out.data_ptr()
         _check(lib().palsgd_diagnostics(self._ctx, ptr, _stream_handle(stream)), self._ctx)
+
+    def palsgd_outer_step_diag(self, t, out, stream=None):
+        """Outer step + diagnostics taken just before it; out as in palsgd_diagnostics."""
+        ptr = out if isinstance(out, int) else out.data_ptr()
+        _check(lib().palsgd_outer_step_diag(self._ctx, int(t), ptr, _stream_handle(stream)), self._ctx)
 
     def palsgd_get_state(self):
         tau = (C.c_uint64 * self.K)()

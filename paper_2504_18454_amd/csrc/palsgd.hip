@@ -198,29 +198,55 @@ __device__ __forceinline__ f4 outer4(f4 dsum, f4 xg, f4& om, const OuterArgs& a)
     return xg - a.lr * dir;
 }
 
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    return v;  // lane 0 holds the sum
+}
+
 // Variant 1: one wavefront per tile; each lane owns four consecutive elements and walks the
 // K rows in ascending order, eight independent loads in flight at a time.
+// DIAG: also leaves, per wavefront, the partial sums of sum_k |x - x_k|^2 and |Delta|^2
+// (App. A.3) taken from the values already in registers: no extra HBM reads.
+template <bool DIAG>
 __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X, float* __restrict__ XG,
                                                            float* __restrict__ OM, uint64_t n,
-                                                           uint64_t row_stride, uint32_t K, OuterArgs a) {
+                                                           uint64_t row_stride, uint32_t K, OuterArgs a,
+                                                           float* __restrict__ partial, uint32_t n_part) {
     const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
-    if (e >= n) return;
-    f4 xg = ld4(XG + e);
-    f4 om = ld4(OM + e);
-    f4 sum = {0.f, 0.f, 0.f, 0.f};
-    for (uint32_t k0 = 0; k0 < K; k0 += 8) {
-        f4 t[8];
+    const bool active = e < n;  // no early exit: every lane takes part in the shuffles
+    f4 sum = {0.f, 0.f, 0.f, 0.f}, sq = {0.f, 0.f, 0.f, 0.f};
+    if (active) {
+        f4 xg = ld4(XG + e);
+        f4 om = ld4(OM + e);
+        for (uint32_t k0 = 0; k0 < K; k0 += 8) {
+            f4 t[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (k0 + u < K) t[u] = ld4(X + (uint64_t)(k0 + u) * row_stride + e);
+            for (int u = 0; u < 8; ++u)
+                if (k0 + u < K) t[u] = ld4(X + (uint64_t)(k0 + u) * row_stride + e);
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (k0 + u < K) sum += xg - t[u];
+            for (int u = 0; u < 8; ++u)
+                if (k0 + u < K) {
+                    f4 d = xg - t[u];
+                    sum += d;
+                    if (DIAG) sq += d * d;
+                }
+        }
+        f4 xn = outer4(sum, xg, om, a);
+        st4(XG + e, xn);
+        st4(OM + e, om);
+        for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
     }
-    f4 xn = outer4(sum, xg, om, a);
-    st4(XG + e, xn);
-    st4(OM + e, om);
-    for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
+    if (DIAG) {
+        const f4 delta = sum * a.inv_k;
+        const f4 dd = delta * delta;
+        float xi = wave_sum((sq.x + sq.y) + (sq.z + sq.w));
+        float d2 = wave_sum((dd.x + dd.y) + (dd.z + dd.w));
+        if (threadIdx.x == 0) {
+            partial[blockIdx.x] = xi;
+            partial[n_part + blockIdx.x] = d2;
+        }
+    }
 }
 
 // Variant 2: a workgroup owns a tile of 4 x 256 elements.  Wave w sums the replicas
@@ -337,12 +363,6 @@ __global__ __launch_bounds__(kWave) void ddp_kernel(const DdpArgs a, const float
 // Reductions to scalars: lane-local accumulation, a shuffle tree inside the wavefront, one
 // partial per wavefront in device scratch, and a second single-workgroup pass that adds the
 // partials in double in a fixed order (deterministic run to run).
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
-    return v;  // lane 0 holds the sum
-}
-
 constexpr int kNormTiles = 16;  // tiles a wavefront of the norm kernel walks: one partial per 4096 elements
 constexpr int kDiagTiles = 8;   // same for the diagnostics kernel: one partial pair per 2048 elements
 
@@ -354,11 +374,17 @@ __global__ __launch_bounds__(kWave) void sumsq_kernel(const void* __restrict__ G
     const uint64_t base = (uint64_t)blockIdx.x * (kTile * kNormTiles) + threadIdx.x * 4;
     const uint64_t row = (uint64_t)blockIdx.y * row_stride;
     float acc = 0.f;
-#pragma unroll 4
+    typename GL::raw r[kNormTiles];  // all loads of the wavefront are issued before the first use
+#pragma unroll
+    for (int u = 0; u < kNormTiles; ++u) {
+        const uint64_t e = base + (uint64_t)u * kTile;
+        if (e < n) r[u] = GL::load(G, row + e);
+    }
+#pragma unroll
     for (int u = 0; u < kNormTiles; ++u) {
         const uint64_t e = base + (uint64_t)u * kTile;
         if (e < n) {
-            f4 g = GL::widen(GL::load(G, row + e));
+            f4 g = GL::widen(r[u]);
             acc += (g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w);
         }
     }
@@ -366,10 +392,17 @@ __global__ __launch_bounds__(kWave) void sumsq_kernel(const void* __restrict__ G
     if (threadIdx.x == 0) partial[(uint64_t)blockIdx.y * per_row + blockIdx.x] = acc;
 }
 
-// Fixed-order sum of `count` floats in double by one workgroup; every thread returns the total.
-__device__ double block_sum(const float* __restrict__ v, uint32_t count, double* lds) {
+// Fixed-order sum of `count` values in double by one workgroup; every thread returns the total.
+template <typename T>
+__device__ double block_sum(const T* __restrict__ v, uint32_t count, double* lds) {
     double acc = 0.0;
-    for (uint32_t j = threadIdx.x; j < count; j += kThreads) acc += (double)v[j];
+    for (uint32_t j = threadIdx.x; j < count; j += 4 * kThreads) {  // four independent loads in flight
+        T t[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t[q] = j + q * kThreads < count ? v[j + q * kThreads] : (T)0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc += (double)t[q];
+    }
     lds[threadIdx.x] = acc;
     __syncthreads();
     for (int s = kThreads / 2; s > 0; s >>= 1) {
@@ -381,13 +414,26 @@ __device__ double block_sum(const float* __restrict__ v, uint32_t count, double*
     return total;
 }
 
+constexpr uint32_t kFold = 128;  // second-stage workgroups per series of partial sums
+
+// Second stage: series y has `count` float partials; workgroup x adds its contiguous slice in double.
+__global__ __launch_bounds__(kThreads) void fold_kernel(const float* __restrict__ partial, uint32_t count,
+                                                        double* __restrict__ fold) {
+    __shared__ double lds[kThreads];
+    const uint32_t slice = (count + kFold - 1) / kFold;
+    const uint32_t begin = blockIdx.x * slice;
+    const uint32_t len = begin >= count ? 0u : (count - begin < slice ? count - begin : slice);
+    double total = block_sum(partial + (uint64_t)blockIdx.y * count + begin, len, lds);
+    if (threadIdx.x == 0) fold[blockIdx.y * kFold + blockIdx.x] = total;
+}
+
 // norm_k = sqrt(sum of squares); scale_k = min(1, max_norm / (norm_k + 1e-6)).  One workgroup per replica.
-__global__ __launch_bounds__(kThreads) void clip_finish_kernel(const float* __restrict__ partial, uint32_t per_row,
-                                                               float max_norm, float* __restrict__ scale,
+__global__ __launch_bounds__(kThreads) void clip_finish_kernel(const double* __restrict__ fold, float max_norm,
+                                                               float* __restrict__ scale,
                                                                float* __restrict__ norms_out) {
     __shared__ double lds[kThreads];
     const uint32_t k = blockIdx.x;
-    double total = block_sum(partial + (uint64_t)k * per_row, per_row, lds);
+    double total = block_sum(fold + k * kFold, kFold, lds);
     if (threadIdx.x == 0) {
         double norm = sqrt(total);
         double c = (double)max_norm / (norm + 1e-6);
@@ -406,13 +452,13 @@ __global__ __launch_bounds__(kWave) void diag_kernel(const float* __restrict__ X
     for (int u = 0; u < kDiagTiles; ++u) {
         const uint64_t e = base + (uint64_t)u * kTile;
         if (e >= n) break;
-        const f4 xg = ld4_cached(XG + e);
+        const f4 xg = ld4(XG + e);
         f4 sum = {0.f, 0.f, 0.f, 0.f}, sq = {0.f, 0.f, 0.f, 0.f};
         for (uint32_t k0 = 0; k0 < K; k0 += 8) {
             f4 t[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q)
-                if (k0 + q < K) t[q] = ld4_cached(X + (uint64_t)(k0 + q) * row_stride + e);
+                if (k0 + q < K) t[q] = ld4(X + (uint64_t)(k0 + q) * row_stride + e);
 #pragma unroll
             for (int q = 0; q < 8; ++q)
                 if (k0 + q < K) {
@@ -434,11 +480,11 @@ __global__ __launch_bounds__(kWave) void diag_kernel(const float* __restrict__ X
     }
 }
 
-__global__ __launch_bounds__(kThreads) void diag_finish_kernel(const float* __restrict__ partial, uint32_t n_part,
-                                                               float inv_k, float* __restrict__ out) {
+__global__ __launch_bounds__(kThreads) void diag_finish_kernel(const double* __restrict__ fold, float inv_k,
+                                                               float* __restrict__ out) {
     __shared__ double lds[kThreads];
-    double xi = block_sum(partial, n_part, lds);
-    double d2 = block_sum(partial + n_part, n_part, lds);
+    double xi = block_sum(fold, kFold, lds);
+    double d2 = block_sum(fold + kFold, kFold, lds);
     if (threadIdx.x == 0) {
         out[0] = (float)(xi * (double)inv_k);
         out[1] = (float)d2;
@@ -562,21 +608,24 @@ palsgd_status check_launch(palsgd_ctx* c, const char* what) {
     return PALSGD_OK;
 }
 
-// Scratch layout: [0, K) clipping scales, [K, K+2) diagnostics staging, then the partial sums.
+// Scratch layout (floats): [0, 64) clipping scales | 64 * kFold doubles of second-stage sums |
+// first-stage partial sums (one per wavefront of the producing kernel).
 uint32_t norm_parts(const palsgd_ctx* c) {
     return (uint32_t)((c->P_padded + (uint64_t)kTile * kNormTiles - 1) / ((uint64_t)kTile * kNormTiles));
 }
 uint32_t diag_parts(const palsgd_ctx* c) {
     return (uint32_t)((c->P_padded + (uint64_t)kTile * kDiagTiles - 1) / ((uint64_t)kTile * kDiagTiles));
 }
+uint32_t tile_count(const palsgd_ctx* c) { return (uint32_t)((c->P_padded + kTile - 1) / kTile); }
 float* clip_scales(palsgd_ctx* c) { return c->d_scratch; }
-float* scratch_partials(palsgd_ctx* c) { return c->d_scratch + PALSGD_MAX_K + 64; }
+double* scratch_fold(palsgd_ctx* c) { return (double*)(c->d_scratch + PALSGD_MAX_K); }
+float* scratch_partials(palsgd_ctx* c) { return c->d_scratch + PALSGD_MAX_K + 2 * PALSGD_MAX_K * kFold; }
 
 palsgd_status ensure_scratch(palsgd_ctx* c) {
     if (c->d_scratch) return PALSGD_OK;
     uint64_t parts = (uint64_t)c->cfg.K * norm_parts(c);
-    if (parts < 2ull * diag_parts(c)) parts = 2ull * diag_parts(c);
-    uint64_t floats = PALSGD_MAX_K + 64 + parts;
+    if (parts < 2ull * tile_count(c)) parts = 2ull * tile_count(c);  // fused diagnostics: two per tile
+    uint64_t floats = PALSGD_MAX_K + 2ull * PALSGD_MAX_K * kFold + parts;
     float* d = nullptr;
     hipError_t e = hipMalloc(&d, floats * sizeof(float));
     if (e != hipSuccess) {
@@ -799,9 +848,9 @@ palsgd_status palsgd_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, float eta_
     return local_update(ctx, "palsgd_step", t, alpha_t, eta_t, grad_scale, mask_override, true, true, stream);
 }
 
-palsgd_status palsgd_outer_step(palsgd_ctx* ctx, uint64_t t, void* stream) {
+static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, float* diag_out_dev, void* stream) {
     if (!ctx) {
-        set_error(g_error, "palsgd_outer_step: NULL context");
+        set_error(g_error, "%s: NULL context", who);
         return PALSGD_EINVAL;
     }
     const uint32_t K = ctx->cfg.K;
@@ -809,23 +858,43 @@ palsgd_status palsgd_outer_step(palsgd_ctx* ctx, uint64_t t, void* stream) {
     const uint64_t n = ctx->P_padded;
     hipStream_t st = (hipStream_t)stream;
     const uint32_t variant = ctx->outer_variant ? ctx->outer_variant : 1u;
-    const uint32_t waves = ctx->outer_waves ? ctx->outer_waves : auto_waves((8u * K + 16u) * kTile, 4);  // K rows are walked 8 at a time: 4 is best from K=16 up
-    if (variant == 2) {
+    const uint32_t waves = ctx->outer_waves ? ctx->outer_waves
+                                            : auto_waves((8u * K + 16u) * kTile, 4);  // rows go 8 at a time: 4 is best from K=16 up
+    const palsgd_buffers& b = ctx->buf;
+    if (diag_out_dev) {
+        palsgd_status rc = ensure_scratch(ctx);
+        if (rc != PALSGD_OK) return rc;
+        const uint32_t tiles = tile_count(ctx);
+        outer_kernel_walk<true><<<tiles, kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, n, b.row_stride, K, a,
+                                                                        scratch_partials(ctx), tiles);
+        fold_kernel<<<dim3(kFold, 2), kThreads, 0, st>>>(scratch_partials(ctx), tiles, scratch_fold(ctx));
+        diag_finish_kernel<<<1, kThreads, 0, st>>>(scratch_fold(ctx), a.inv_k, diag_out_dev);
+    } else if (variant == 2) {
         const uint64_t n4 = n / 4;
         uint32_t blocks = (uint32_t)((n4 + 255) / 256);
         uint32_t groups = waves / 4 ? waves / 4 : 1;  // a workgroup of this variant is four wavefronts
-        outer_kernel_lds<<<blocks, kThreads, lds_cap(groups, 16384), st>>>(ctx->buf.X, ctx->buf.XG, ctx->buf.OM, n4,
-                                                                           ctx->buf.row_stride, K, a);
+        outer_kernel_lds<<<blocks, kThreads, lds_cap(groups, 16384), st>>>(b.X, b.XG, b.OM, n4, b.row_stride, K, a);
     } else {
-        uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
-        outer_kernel_walk<<<tiles, kWave, lds_cap(waves, 0), st>>>(ctx->buf.X, ctx->buf.XG, ctx->buf.OM, n,
-                                                                   ctx->buf.row_stride, K, a);
+        outer_kernel_walk<false><<<tile_count(ctx), kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, n, b.row_stride,
+                                                                                 K, a, nullptr, 0);
     }
-    palsgd_status rc = check_launch(ctx, "palsgd_outer_step");
+    palsgd_status rc = check_launch(ctx, who);
     if (rc != PALSGD_OK) return rc;
     ctx->n_outer += 1;
     ctx->last_outer_t = t;
     return PALSGD_OK;
+}
+
+palsgd_status palsgd_outer_step(palsgd_ctx* ctx, uint64_t t, void* stream) {
+    return outer_impl(ctx, "palsgd_outer_step", t, nullptr, stream);
+}
+
+palsgd_status palsgd_outer_step_diag(palsgd_ctx* ctx, uint64_t t, float* diag_out_dev, void* stream) {
+    if (ctx && !diag_out_dev) {
+        set_error(ctx->error, "palsgd_outer_step_diag: NULL output");
+        return PALSGD_EINVAL;
+    }
+    return outer_impl(ctx, "palsgd_outer_step_diag", t, diag_out_dev, stream);
 }
 
 palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const float* grad_scale, void* stream) {
@@ -907,12 +976,13 @@ palsgd_status palsgd_clip_grad_norm(palsgd_ctx* ctx, float max_norm, float* norm
     hipStream_t st = (hipStream_t)stream;
     dim3 grid(per_row, K);
     if (ctx->cfg.grad_dtype == PALSGD_GRAD_BF16)
-        sumsq_kernel<PALSGD_GRAD_BF16><<<grid, kWave, 0, st>>>(ctx->buf.G, scratch_partials(ctx), ctx->P_padded,
+        sumsq_kernel<PALSGD_GRAD_BF16><<<grid, kWave, lds_cap(16, 0), st>>>(ctx->buf.G, scratch_partials(ctx), ctx->P_padded,
                                                                ctx->buf.row_stride, per_row);
     else
-        sumsq_kernel<PALSGD_GRAD_F32><<<grid, kWave, 0, st>>>(ctx->buf.G, scratch_partials(ctx), ctx->P_padded,
+        sumsq_kernel<PALSGD_GRAD_F32><<<grid, kWave, lds_cap(16, 0), st>>>(ctx->buf.G, scratch_partials(ctx), ctx->P_padded,
                                                               ctx->buf.row_stride, per_row);
-    clip_finish_kernel<<<K, kThreads, 0, st>>>(scratch_partials(ctx), per_row, max_norm, clip_scales(ctx), norms_out_dev);
+    fold_kernel<<<dim3(kFold, K), kThreads, 0, st>>>(scratch_partials(ctx), per_row, scratch_fold(ctx));
+    clip_finish_kernel<<<K, kThreads, 0, st>>>(scratch_fold(ctx), max_norm, clip_scales(ctx), norms_out_dev);
     rc = check_launch(ctx, "palsgd_clip_grad_norm");
     if (rc != PALSGD_OK) return rc;
     ctx->clip_armed = true;
@@ -931,7 +1001,8 @@ palsgd_status palsgd_diagnostics(palsgd_ctx* ctx, float* out_dev, void* stream) 
     hipStream_t st = (hipStream_t)stream;
     diag_kernel<<<n_part, kWave, 0, st>>>(ctx->buf.X, ctx->buf.XG, scratch_partials(ctx), ctx->P_padded,
                                           ctx->buf.row_stride, K, inv_k, n_part);
-    diag_finish_kernel<<<1, kThreads, 0, st>>>(scratch_partials(ctx), n_part, inv_k, out_dev);
+    fold_kernel<<<dim3(kFold, 2), kThreads, 0, st>>>(scratch_partials(ctx), n_part, scratch_fold(ctx));
+    diag_finish_kernel<<<1, kThreads, 0, st>>>(scratch_fold(ctx), inv_k, out_dev);
     return check_launch(ctx, "palsgd_diagnostics");
 }
 

@@ -128,7 +128,7 @@ class Run:
         for k in range(K):
             self.G[k].index_copy_(0, self.idx_dev, gd[k])
 
-    def iterate(self, steps, *, fused=True, grad_scale=None, mask_fn=None, check_every=0, clip=None):
+    def iterate(self, steps, *, fused=True, grad_scale=None, mask_fn=None, check_every=0, clip=None, diag_outer=False):
         for _ in range(steps):
             t = self.t
             self.make_gradients()
@@ -144,7 +144,15 @@ class Run:
                 scales = np.array([oracle.clip_scale(v, float(np.float32(clip))) for v in norms])
                 gs64 = scales if gs64 is None else gs64 * scales
                 self.last_scales = scales
-            mask_o, synced = self.ora.iteration(t, self.alpha, self.eta, grad_scale=gs64, mask_override=mo)
+            if diag_outer:                 # oracle: local update, diagnostics, then the outer step
+                assert self.full
+                mask_o = self.ora.local_step(t, self.alpha, self.eta, grad_scale=gs64, mask_override=mo)
+                synced = (t + 1) % self.H == 0
+                if synced:
+                    want_diag = self.ora.diagnostics()
+                    self.ora.outer_step()
+            else:
+                mask_o, synced = self.ora.iteration(t, self.alpha, self.eta, grad_scale=gs64, mask_override=mo)
             if mo is None:
                 assert np.array_equal(self.lib.palsgd_draw(t), mask_o), f"draws differ at t={t}"
             if fused:
@@ -154,7 +162,14 @@ class Run:
                 self.lib.palsgd_inner_step(t, self.alpha, grad_scale, mo)
             if (t + 1) % self.H == 0:
                 assert synced
-                self.lib.palsgd_outer_step(t)
+                if diag_outer:
+                    out = torch.empty(2, dtype=torch.float32, device=self.dev)
+                    self.lib.palsgd_outer_step_diag(t, out)
+                    # both sides sum their own fp32 state (equal to 1e-5 relative), hence the slack
+                    np.testing.assert_allclose(out.cpu().numpy(), want_diag, rtol=2e-3, atol=1e-12)
+                    self.last_diag = want_diag
+                else:
+                    self.lib.palsgd_outer_step(t)
             self.t += 1
             if check_every and self.t % check_every == 0:
                 self.compare()

@@ -72,6 +72,15 @@ def test_diagnostics_in_the_loop_and_zero_after_sync():
     r.close()
 
 
+@pytest.mark.parametrize("K", [1, 4, 16])
+def test_outer_step_with_fused_diagnostics(K):
+    r = _run(K=K, numels=RAGGED, p=0.2, H=3, seed=34 + K, sigma=0.05, row_extra=1)
+    r.iterate(10, diag_outer=True)
+    r.compare()
+    assert r.last_diag[0] > 0
+    r.close()
+
+
 def _full_row_inputs(name, seed):
     w = workload(name)
     from paper_2504_18454_amd import make_config, palsgd_layout
@@ -112,6 +121,9 @@ def test_reductions_full_size_on_seeded_inputs(name):
         assert float(norms[k]) == pytest.approx(oracle.grad_norm(np.ascontiguousarray(g)), rel=1e-5)
     xi, d2 = oracle.diagnostics(X.cpu().numpy(), XG.cpu().numpy())
     assert out.cpu().tolist() == pytest.approx([xi, d2], rel=1e-5)
+    out2 = torch.empty(2, dtype=f, device=dev)
+    lib.palsgd_outer_step_diag(0, out2)                 # same inputs: the fused reduction must give the same scalars
+    assert out2.cpu().tolist() == pytest.approx([xi, d2], rel=1e-5)
     lib.palsgd_destroy()
 
 
