@@ -46,7 +46,7 @@ typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 constexpr int kWave = 64;            // lanes of a wavefront = threads of a streaming workgroup
 constexpr int kTile = kWave * 4;     // elements a wavefront covers with one 16-byte group per lane
 constexpr int kThreads = 256;        // workgroup of the LDS-staged outer variant and of init
-constexpr uint32_t kLdsPerCU = 160u * 1024u;
+constexpr uint32_t kLdsPerCUDefault = 160u * 1024u;  // gfx950; the device is asked at the first launch
 constexpr uint32_t kInflightDefault = 72u * 1024u;  // bytes of loads+stores in flight per CU
 
 // Per-launch, per-slot scalars; slot s of the grid's y dimension works on row `replica`.
@@ -586,9 +586,25 @@ palsgd_status build_wd_table(palsgd_ctx* c) {
 
 // LDS bytes to request per workgroup so that at most `groups` workgroups are resident on a
 // CU (0 = no cap).  The kernels use none of it: the allocation is the occupancy throttle.
+uint32_t g_lds_per_cu = 0;
+
+uint32_t lds_per_cu() {
+    if (g_lds_per_cu == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) == hipSuccess &&
+            v >= 65536)
+            g_lds_per_cu = (uint32_t)v;
+        else
+            g_lds_per_cu = kLdsPerCUDefault;
+        (void)hipGetLastError();
+    }
+    return g_lds_per_cu;
+}
+
 uint32_t lds_cap(uint32_t groups, uint32_t static_lds) {
     if (groups == 0 || groups >= 32) return 0;
-    uint32_t l = kLdsPerCU / groups / 512u * 512u;
+    uint32_t l = lds_per_cu() / groups / 512u * 512u;
     if (l > 65536u) l = 65536u;
     return l > static_lds ? l - static_lds : 0;
 }

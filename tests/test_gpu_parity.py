@@ -163,3 +163,32 @@ def test_config_gptneo1p3b_k8_sampled():
     if free < 200 * 2 ** 30:
         pytest.skip("needs about 200 GB of free device memory")
     _sampled("gptneo1p3b_k8", steps=66, per_edge=256, n_random=1 << 16)
+
+
+def test_deterministic_and_stream_independent():
+    """Same inputs give bit-identical results run to run, on the default stream and on two contexts that
+    work concurrently on two side streams (fixed summation orders, no atomics)."""
+    def once(streams):
+        runs = [_run(K=6, numels=RAGGED, grad_dtype="bf16", p=0.3, H=3, seed=21, sigma=0.05) for _ in streams]
+        outs = []
+        for _ in range(7):
+            for r in runs:
+                r.make_gradients()
+            torch.cuda.synchronize()
+            for r, s in zip(runs, streams):
+                t = r.t
+                r.ora.iteration(t, r.alpha, r.eta)
+                r.lib.palsgd_step(t, r.alpha, r.eta, None, None, s)
+                if (t + 1) % r.H == 0:
+                    r.lib.palsgd_outer_step(t, s)
+                r.t += 1
+            torch.cuda.synchronize()
+        for r in runs:
+            r.compare()
+            outs.append([x.clone() for x in (r.X, r.M, r.V, r.XG, r.OM)])
+            r.close()
+        return outs
+    a = once([None])[0]
+    b, c = once([torch.cuda.Stream(), torch.cuda.Stream()])
+    for ta, tb, tc in zip(a, b, c):
+        assert torch.equal(ta, tb) and torch.equal(ta, tc)
