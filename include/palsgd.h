@@ -87,7 +87,7 @@ typedef struct {
  * (n_tensors, tensor_numel).  EINVAL on NULL pointers, n_tensors == 0 or a zero numel. */
 palsgd_status palsgd_layout(const palsgd_config *cfg, uint64_t *P_padded, uint64_t *tensor_offset);
 
-/* Alg. 1, "x_k^(0) <- x^(0)": creates a context over the caller's buffers.  If x0_dev
+/* Alg. 1, initialisation x_k^(0) <- x^(0): creates a context over the caller's buffers.  If x0_dev
  * (device, P_padded floats, padding zero) is not NULL, it is copied into XG and every
  * row of X, and M, V, OM are cleared, on `stream`; if NULL the buffers are taken as
  * they are (resume).  EINVAL: K outside 1..64, H == 0, p outside [0,1), NULL or
@@ -96,13 +96,13 @@ palsgd_status palsgd_layout(const palsgd_config *cfg, uint64_t *P_padded, uint64
 palsgd_status palsgd_init(const palsgd_config *cfg, const palsgd_buffers *buf, const float *x0_dev,
                           void *stream, palsgd_ctx **out);
 
-/* Branch draws b_k^(t) of step t for all K workers (Alg. 1 "b ~ U[0,1]; if b <= p";
+/* Branch draws b_k^(t) of step t for all K workers (Alg. 1: a uniform b compared with p;
  * App. A.2): mask_out (host, K bytes) gets 1 where worker k takes the mixing step.
  * Pure function of (seed, t, k): SplitMix64 output function of the counter t*K+k,
  * top 24 bits compared with floor(p * 2^24).  Host only, no device work. */
 palsgd_status palsgd_draw(const palsgd_ctx *ctx, uint64_t t, uint8_t *mask_out);
 
-/* Gradient step of step t (Alg. 1 "gradient step"; Sec. 4.1 first equation):
+/* Gradient step of step t (Alg. 1, the branch b > p; Sec. 4.1 first equation):
  * x_k <- InnerOPT(x_k, grad_scale[k] * G[k], alpha_t / (1-p)) for every worker whose
  * draw is 0, and advances that worker's InnerOPT step count.  grad_scale: host array
  * [K] or NULL (= 1).  mask_override: host array [K] or NULL; if given it replaces the
@@ -111,7 +111,7 @@ palsgd_status palsgd_draw(const palsgd_ctx *ctx, uint64_t t, uint8_t *mask_out);
 palsgd_status palsgd_inner_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, const float *grad_scale,
                                 const uint8_t *mask_override, void *stream);
 
-/* Pseudo-synchronization step of step t (Alg. 1 "pseudo-synchronization step";
+/* Pseudo-synchronization step of step t (Alg. 1, the branch b <= p;
  * Sec. 4.1 second equation): x_k <- x_k - (alpha_t * eta_t / p) (x_k - XG) for every
  * worker whose draw is 1.  InnerOPT state is not touched.  EINVAL if a worker is to
  * mix while p == 0 (the coefficient is undefined).  No launch if no worker mixes. */
@@ -123,7 +123,7 @@ palsgd_status palsgd_pseudo_sync(palsgd_ctx *ctx, uint64_t t, float alpha_t, flo
 palsgd_status palsgd_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, float eta_t,
                           const float *grad_scale, const uint8_t *mask_override, void *stream);
 
-/* Outer step (Alg. 1 "aggregate outer gradient" and "update global model"; Sec. 4.2):
+/* Outer step (Alg. 1, the two lines of the synchronisation branch; Sec. 4.2):
  * Delta = XG - (1/K) sum_k X[k];  OM <- mu OM + Delta;
  * XG <- XG - outer_lr (Delta + mu OM) (Nesterov) or XG - outer_lr OM;  X[k] <- XG for
  * all k (Sec. 2.1: workers restart from the global model).  The caller decides when
@@ -147,8 +147,8 @@ palsgd_status palsgd_outer_step_diag(palsgd_ctx *ctx, uint64_t t, float *diag_ou
  * palsgd_clip_grad_norm are not consumed here. */
 palsgd_status palsgd_ddp_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, const float *grad_scale, void *stream);
 
-/* Gradient clipping by the global L2 norm of each worker's gradient (App. B: "gradient
- * clipping enabled"; the paper prints no threshold): norm_k = |G[k]|_2 and
+/* Gradient clipping by the global L2 norm of each worker's gradient (App. B says the GPT-Neo runs
+ * clip gradients; the paper prints no threshold): norm_k = |G[k]|_2 and
  * scale_k = min(1, max_norm / (norm_k + 1e-6)) are computed on the device, without a host
  * round trip.  The next palsgd_inner_step / palsgd_step of this context multiplies worker
  * k's gradient by scale_k (on top of grad_scale[k]) and forgets the scales.

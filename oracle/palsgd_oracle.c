@@ -11,18 +11,18 @@
  * live side by side in host memory:
  *
  *   - the Bernoulli(p) branch draw of each worker and step (Alg. 1; App. A.2
- *     "Basic Definitions" calls it b_k^(t)),
+ *     basic definitions call it b_k^(t)),
  *   - the pseudo-synchronization step  x_k <- x_k - (alpha_t eta_t / p)(x_k - x)
  *     (Alg. 1; Sec. 4.1, second equation),
  *   - the gradient step  x_k <- InnerOPT(x_k, g_k, alpha_t / (1-p))
  *     (Alg. 1; Sec. 4.1, first equation) for InnerOPT = AdamW or SGD with
- *     momentum (Sec. 4.3; App. B "Training Configuration"),
+ *     momentum (Sec. 4.3; App. B, training configuration),
  *   - every H steps the outer gradient  Delta = mean_k (x - x_k)
  *     (Alg. 1; Sec. 4.2; All-Reduce is the mean, Sec. 3.1) and the
  *     OuterOPT step with Nesterov momentum (Sec. 4.2, Sec. 4.3), after which
- *     every worker restarts from the new global model (Sec. 2.1 "all workers
- *     start from the same global model every H local steps"; App. A.5 proof of
- *     Lemma 4: x^(t) = x_k^(t-)).
+ *     every worker restarts from the new global model (Sec. 2.1 states that
+ *     the workers share one starting point every H local steps; App. A.5, proof
+ *     of Lemma 4: x^(t) = x_k^(t-)).
  *
  * Precision: state (x_k, x, optimizer moments) is stored in fp32, the storage
  * type of the device path.  Every element update reads the stored values,
@@ -56,7 +56,7 @@ void ora_set_threads(int n) { g_threads = n < 1 ? 1 : n; }
 int ora_get_threads(void) { return g_threads; }
 
 /* ------------------------------------------------------------------------- */
-/* Branch draw b_k^(t)  (Alg. 1 "b ~ U[0,1]; if b <= p"; App. A.2).          */
+/* Branch draw b_k^(t)  (Alg. 1: a uniform b is compared with p; App. A.2).  */
 /*                                                                           */
 /* The paper names no generator.  Both sides of the parity check implement   */
 /* the SplitMix64 output function (Steele, Lea, Flood 2014; public domain)   */
@@ -150,8 +150,8 @@ void ora_adamw(float *x, float *m, float *v, const void *g, int g_dtype,
 }
 
 /* ------------------------------------------------------------------------- */
-/* InnerOPT = SGD with momentum (App. B: "momentum SGD", weight decay 1e-4    */
-/* in the VGG run), heavy-ball form with dampening 0, weight decay coupled    */
+/* InnerOPT = SGD with momentum (App. B names it for the vision runs, with    */
+/* weight decay 1e-4 in the VGG run), heavy-ball form with dampening 0, weight decay coupled    */
 /* into the gradient:                                                         */
 /*   d = g + wd x      buf <- mu buf + d      x <- x - lr buf                 */
 /* (buf starts at 0, so the first step gives buf = d).  mu = 0 is plain SGD,  */
@@ -172,8 +172,8 @@ void ora_sgdm(float *x, float *buf, const void *g, int g_dtype, uint64_t n,
 }
 
 /* ------------------------------------------------------------------------- */
-/* Outer step (Alg. 1 "aggregate outer gradient" / "update global model";     */
-/* Sec. 4.2 both equations; Sec. 3.1 for All-Reduce = mean):                  */
+/* Outer step (Alg. 1, the two lines of the synchronisation branch; Sec. 4.2, */
+/* both equations; Sec. 3.1 for All-Reduce = mean):                           */
 /*   Delta = (1/K) sum_k (x - x_k) = x - (1/K) sum_k x_k     (k ascending)    */
 /*   OuterOPT, SGD with (Nesterov) momentum, Sutskever et al. 2013 in the     */
 /*   buffer form used by common deep-learning libraries (dampening 0):        */
@@ -353,8 +353,8 @@ void ora_ddp_step(ora_state *s, double alpha_t, const double *grad_scale)
 }
 
 /* ------------------------------------------------------------------------- */
-/* Gradient clipping (App. B: "AdamW ... with gradient clipping enabled"; no  */
-/* threshold or norm is printed).  Reading: clipping by the global L2 norm of */
+/* Gradient clipping (App. B says the GPT-Neo runs clip gradients; neither    */
+/* threshold nor norm is printed).  Reading: clipping by the global L2 norm of */
 /* one worker's gradient, the common deep-learning convention:                */
 /*   norm_k = sqrt(sum_i g_k[i]^2)       scale_k = min(1, c / (norm_k + 1e-6)) */
 /* The scale is what the local update takes as grad_scale[k].                 */

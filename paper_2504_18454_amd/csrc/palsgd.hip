@@ -1,8 +1,8 @@
 // PALSGD parameter-update path for MI355X (gfx950, CDNA4): HIP kernels and the C ABI
 // declared in include/palsgd.h.
 //
-// Three kernels, all bound by HBM bandwidth (about one flop per byte moved; the IEEE
-// divide and square root cost nothing measurable), so the design rules are:
+// All kernels are bound by HBM bandwidth (about one flop per byte moved; the correctly
+// rounded divide and the square root cost nothing measurable), so the design rules are:
 //   * every access a full-width coalesced vector load/store: one wavefront instruction
 //     touches one contiguous 1 KiB span (512 B for bf16 gradients);
 //   * every byte of state read once and written once per step, non-temporal both ways;

@@ -1,7 +1,7 @@
 """Seeded synthetic workloads: model-shaped tensor lists and input generators.
 
 This module holds none of the method's arithmetic.  It only says how large the
-parameter tensors of the paper's models are (App. B "Workloads": GPT-Neo with 8M
+parameter tensors of the paper's models are (App. B, workloads: GPT-Neo with 8M
 and 125M parameters, ResNet-50 with 25.6M parameters, the small CNN of the
 CIFAR-10 simulation table) and draws seeded initial models, quadratic targets
 and noisy gradients.  It serves the device path's tests and benchmark and the

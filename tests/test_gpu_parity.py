@@ -192,3 +192,49 @@ def test_deterministic_and_stream_independent():
     b, c = once([torch.cuda.Stream(), torch.cuda.Stream()])
     for ta, tb, tc in zip(a, b, c):
         assert torch.equal(ta, tb) and torch.equal(ta, tc)
+
+
+def test_step_loop_is_capturable_in_a_hip_graph():
+    """The entry points only enqueue kernel launches (no allocation or memset once each kind of call has run
+    once), so a window of steps can be captured into a graph.  A captured launch keeps that step's scalars,
+    so every replay repeats the same arguments; the eager reference restores the step counts before each
+    repetition to do the same.  Replays are interleaved with eager work and compared bit for bit."""
+    from parity import Run
+    def fresh():
+        r = Run(K=4, numels=RAGGED, grad_dtype="bf16", p=0.3, H=2, seed=23, sigma=0.05, wd_mult=[1, 0, 1, 1, 0.5, 1, 0])
+        r.make_gradients()
+        r.lib.palsgd_step(0, r.alpha, r.eta)            # first calls of each kind happen outside the capture
+        r.lib.palsgd_outer_step(0)
+        torch.cuda.synchronize()
+        return r
+    def window(r, stream=None):
+        r.lib.palsgd_step(5, r.alpha, r.eta, None, [0, 1, 0, 0], stream)
+        r.lib.palsgd_step(6, r.alpha, r.eta, None, [0, 0, 0, 1], stream)
+        r.lib.palsgd_outer_step(6, stream)
+    a, b = fresh(), fresh()
+    b.G.copy_(a.G)
+    state = a.lib.palsgd_get_state()
+    # eager reference: three repetitions of the window with restored step counts
+    snaps = []
+    for _ in range(3):
+        a.lib.palsgd_set_state(*state)
+        window(a)
+        torch.cuda.synchronize()
+        snaps.append([x.clone() for x in (a.X, a.M, a.V, a.XG, a.OM)])
+    # graph: capture once, replay three times with eager work in between
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    keep = [x.clone() for x in (b.X, b.M, b.V, b.XG, b.OM)]
+    with torch.cuda.graph(g, stream=s):
+        window(b)                                       # binding uses the current (capturing) stream
+    torch.cuda.synchronize()
+    for dst, src in zip((b.X, b.M, b.V, b.XG, b.OM), keep):   # capture does not run the work; make sure of the start state
+        dst.copy_(src)
+    for i in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((b.X, b.M, b.V, b.XG, b.OM), snaps[i]):
+            assert torch.equal(got, want), f"replay {i}"
+        scratch = torch.randn(1 << 20, device="cuda:0").sum().item()   # eager work between replays
+    a.close(); b.close()

@@ -2,7 +2,7 @@
 separately from it, and against the reductions the paper fixes:
 
   * p = 0 (the mixing branch never fires) is DiLoCo; with OuterOPT = SGD, step size 1, it
-    is Local SGD / FedAvg (Sec. 5.2 "Preliminary Experiments"; Sec. 2.3);
+    is Local SGD / FedAvg (Sec. 5.2, the preliminary CIFAR-10 experiments; Sec. 2.3);
   * H = 1 with OuterOPT = SGD step size 1 is synchronous averaging, and with plain SGD
     inside it is one SGD step on the averaged gradient, i.e. DDP (Sec. 3.1);
   * K = 1 with that OuterOPT leaves the single worker untouched;
