@@ -59,7 +59,7 @@ def grad_bytes_per_elem(inner: str, grad_dtype: str) -> int:
     return (24 if inner == "adamw" else 16) + g          # read+write x,m(,v) + read g
 
 
-def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=False):
+def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=False, graph=False):
     import torch
 
     from paper_2504_18454_amd import Palsgd, make_config, palsgd_layout
@@ -152,6 +152,28 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
         blended_gbps=total_bytes / elapsed / 1e9,
     )
     torch.cuda.synchronize()
+    if graph:
+        # the same steps through the device-resident schedule, one captured window of H steps + outer step replayed
+        ae = torch.tensor([w.alpha, w.eta], dtype=f, device=dev)
+        ctx.palsgd_capturable_begin(warmup + steps, stream)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=stream):
+            for _ in range(w.H):
+                ctx.palsgd_step_capturable(ae)
+            ctx.palsgd_outer_step(0)
+        torch.cuda.synchronize()
+        windows = max(1, steps // w.H)
+        gr.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(windows):
+            gr.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ctx.palsgd_capturable_end(stream)
+        res["graph"] = dict(windows=windows, ms_per_step=dt / (windows * w.H) * 1e3,
+                            value=float(K) * P * windows * w.H / dt)
     if extra:
         # the kernels next to the hot path, each timed alone with events on the launch stream
         def timed(fn, reps=10):
@@ -221,6 +243,8 @@ def main():
     ap.add_argument("--outer-waves", type=int, default=0, help="resident wavefronts per CU, outer step (0 = library's choice)")
     ap.add_argument("--outer-variant", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time windows of H steps + outer step replayed from one HIP graph (device-resident schedule)")
     ap.add_argument("--extra-kernels", action="store_true",
                     help="also time the DDP warm-up step, gradient-norm clipping and diagnostics kernels")
     a = ap.parse_args()
@@ -230,7 +254,7 @@ def main():
         sys.exit(2)
     from paper_2504_18454_amd.workloads import workload
     w = workload(a.workload)
-    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels)
+    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph)
     cpu = None if a.no_cpu_baseline else run_cpu_baseline(w)
     gb = grad_bytes_per_elem(w.inner, w.grad_dtype)
     out = {
@@ -251,6 +275,8 @@ def main():
                          "bytes_per_elem": 8 * w.K + 16},
         "cpu_baseline": cpu,
     }
+    if a.graph:
+        out["hip_graph_replay"] = r["graph"]
     if a.extra_kernels:
         out["extra_kernels"] = {k: r[k] for k in ("ddp_step", "clip_grad_norm", "diagnostics")}
     print(json.dumps(out))

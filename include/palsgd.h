@@ -22,7 +22,8 @@
  * Ownership: the library borrows the buffer pointers from palsgd_init until
  * palsgd_destroy and owns only its context, a device-side table of weight-decay
  * values (4 bytes per 64 elements of a row, made by the first gradient step and only
- * when tensor_wd_mult is not uniform) and the scratch of the scalar reductions.
+ * when tensor_wd_mult is not uniform), the scratch of the scalar reductions and the
+ * device schedule of the capturable mode.
  * Streams: `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
  * device work is enqueued on it; calls return without waiting.
  * Errors: every entry point returns a palsgd_status and never aborts; argument
@@ -164,6 +165,29 @@ palsgd_status palsgd_clip_grad_norm(palsgd_ctx *ctx, float max_norm, float *norm
  * with Delta = XG - (1/K) sum_k x_k, the outer gradient of Sec. 4.2.  out_dev: device
  * array of 2 floats.  Nothing else is modified.  Sums are formed in a fixed order. */
 palsgd_status palsgd_diagnostics(palsgd_ctx *ctx, float *out_dev, void *stream);
+
+/* Device-resident schedule, for callers that capture their training step in a HIP graph
+ * (a captured launch keeps its arguments, so nothing that changes per step may be one).
+ * Between palsgd_capturable_begin and palsgd_capturable_end the step index t, the branch
+ * draws b_k^(t) (same hash as palsgd_draw), each worker's InnerOPT step count and AdamW
+ * bias corrections live in library-owned device memory and are advanced on the device.
+ *
+ * palsgd_capturable_begin: uploads t0 (index of the next step) and the current step counts;
+ *   allocates the device schedule on its first call, so call it before the capture starts.
+ * palsgd_step_capturable: step t of Alg. 1 for all K workers, as palsgd_step with
+ *   grad_scale == NULL and no mask override, then t <- t+1, in two launches.  alpha_eta_dev:
+ *   device array {alpha_t, eta_t}, read when the step runs (the caller may update it between
+ *   replays: learning-rate schedules).  Clipping scales armed at the time of the call are
+ *   applied.  Safe to capture; palsgd_outer_step, palsgd_outer_step_diag,
+ *   palsgd_clip_grad_norm and palsgd_diagnostics are capturable as they are (their first
+ *   calls allocate, so make one call of each kind used before the capture).
+ * palsgd_capturable_end: waits for `stream`, reads t and the step counts back (t_out may be
+ *   NULL) and returns the context to host-driven calls.
+ * While the schedule is device-resident, palsgd_inner_step, palsgd_pseudo_sync, palsgd_step,
+ * palsgd_ddp_step, palsgd_get_state and palsgd_set_state return ESTATE. */
+palsgd_status palsgd_capturable_begin(palsgd_ctx *ctx, uint64_t t0, void *stream);
+palsgd_status palsgd_step_capturable(palsgd_ctx *ctx, const float *alpha_eta_dev, void *stream);
+palsgd_status palsgd_capturable_end(palsgd_ctx *ctx, uint64_t *t_out, void *stream);
 
 /* Host-side scalar state for checkpoint / resume: tau[k] = gradient steps worker k
  * has taken (drives AdamW's bias correction), n_outer = outer steps taken. */

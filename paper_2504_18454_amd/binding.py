@@ -25,7 +25,8 @@ MAX_K = 64
 EXPORTS = ("palsgd_layout", "palsgd_init", "palsgd_draw", "palsgd_inner_step", "palsgd_pseudo_sync",
            "palsgd_step", "palsgd_outer_step", "palsgd_get_state", "palsgd_set_state",
            "palsgd_last_error", "palsgd_destroy", "palsgd_set_tuning", "palsgd_ddp_step",
-           "palsgd_clip_grad_norm", "palsgd_diagnostics", "palsgd_outer_step_diag")
+           "palsgd_clip_grad_norm", "palsgd_diagnostics", "palsgd_outer_step_diag", "palsgd_capturable_begin",
+           "palsgd_step_capturable", "palsgd_capturable_end")
 
 
 class PalsgdError(RuntimeError):
@@ -82,6 +83,12 @@ def lib() -> C.CDLL:
         L.palsgd_clip_grad_norm.argtypes = [vp, f, vp, vp]
         L.palsgd_diagnostics.restype = st
         L.palsgd_diagnostics.argtypes = [vp, vp, vp]
+        L.palsgd_capturable_begin.restype = st
+        L.palsgd_capturable_begin.argtypes = [vp, u64, vp]
+        L.palsgd_step_capturable.restype = st
+        L.palsgd_step_capturable.argtypes = [vp, vp, vp]
+        L.palsgd_capturable_end.restype = st
+        L.palsgd_capturable_end.argtypes = [vp, C.POINTER(u64), vp]
         L.palsgd_outer_step_diag.restype = st
         L.palsgd_outer_step_diag.argtypes = [vp, u64, vp, vp]
         L.palsgd_get_state.restype = st
@@ -219,6 +226,19 @@ class Palsgd:
         """Outer step + diagnostics taken just before it; out as in palsgd_diagnostics."""
         ptr = out if isinstance(out, int) else out.data_ptr()
         _check(lib().palsgd_outer_step_diag(self._ctx, int(t), ptr, _stream_handle(stream)), self._ctx)
+
+    def palsgd_capturable_begin(self, t0, stream=None):
+        _check(lib().palsgd_capturable_begin(self._ctx, int(t0), _stream_handle(stream)), self._ctx)
+
+    def palsgd_step_capturable(self, alpha_eta, stream=None):
+        """alpha_eta: torch CUDA float32 tensor {alpha_t, eta_t} (or a device address)."""
+        ptr = alpha_eta if isinstance(alpha_eta, int) else alpha_eta.data_ptr()
+        _check(lib().palsgd_step_capturable(self._ctx, ptr, _stream_handle(stream)), self._ctx)
+
+    def palsgd_capturable_end(self, stream=None) -> int:
+        t = C.c_uint64(0)
+        _check(lib().palsgd_capturable_end(self._ctx, C.byref(t), _stream_handle(stream)), self._ctx)
+        return int(t.value)
 
     def palsgd_get_state(self):
         tau = (C.c_uint64 * self.K)()

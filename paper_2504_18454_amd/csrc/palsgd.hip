@@ -130,14 +130,17 @@ __device__ __forceinline__ void sgdm4(f4& x, f4& b, f4 g, float mu, float lr, fl
 // takes one tile (256 elements: 6.5-7 KiB of traffic); a mixing wavefront takes two (6 KiB),
 // so that both kinds keep about the same number of bytes in flight.
 // TAB: weight decay comes from a table with one entry per 64 elements of a row.
-template <int INNER, int GDT, bool TAB>
-__global__ __launch_bounds__(kWave) void step_kernel(const StepArgs args, const float* __restrict__ wd_tab,
-                                                     float* __restrict__ X, float* __restrict__ M,
+// DEV: the per-slot scalars come from device memory (dev_slots, written by plan_kernel for
+// this step) instead of the kernel arguments.  A compile-time switch: selecting the source
+// at run time turns the scalar loads and the uniform branch into vector ones (-10 %).
+template <int INNER, int GDT, bool TAB, bool DEV>
+__global__ __launch_bounds__(kWave) void step_kernel(const StepArgs args, const Slot* __restrict__ dev_slots,
+                                                     const float* __restrict__ wd_tab, float* __restrict__ X, float* __restrict__ M,
                                                      float* __restrict__ V, const void* __restrict__ G,
                                                      const float* __restrict__ XG,
                                                      const float* __restrict__ clip_scale, uint64_t n,
                                                      uint64_t row_stride, Hyper h) {
-    const Slot sl = args.s[blockIdx.y];
+    const Slot sl = DEV ? dev_slots[blockIdx.y] : args.s[blockIdx.y];
     const uint64_t row = (uint64_t)sl.replica * row_stride;
     const uint32_t lane4 = threadIdx.x * 4;
 
@@ -311,6 +314,72 @@ __global__ __launch_bounds__(kThreads) void init_kernel(const float* __restrict_
         st4(M + r, z);
         if (V) st4(V + r, z);
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Device-resident schedule, for callers that capture their training step in a HIP graph: a
+// captured launch keeps its arguments, so everything that changes from step to step (the
+// step index t, the branch draws, each worker's InnerOPT step count and bias corrections,
+// alpha_t and eta_t) lives in device memory and is advanced by plan_kernel, one lane per
+// worker, right before each local update.
+struct DevSchedule {
+    uint64_t t;                  // index of the next step
+    uint64_t tau[PALSGD_MAX_K];  // gradient steps taken per worker
+    Slot slot[PALSGD_MAX_K];     // scalars of the step about to run
+};
+
+struct PlanArgs {
+    uint64_t seed;
+    double p, beta1, beta2;
+    uint32_t K, threshold, adamw;
+};
+
+// SplitMix64 output function as a counter hash (Steele, Lea, Flood 2014), top 24 bits.
+__host__ __device__ inline uint32_t draw_u24(uint64_t seed, uint64_t t, uint32_t k, uint32_t K) {
+    uint64_t z = seed + (t * (uint64_t)K + k + 1ull) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return (uint32_t)(z >> 40);
+}
+
+__global__ __launch_bounds__(kWave) void plan_kernel(DevSchedule* __restrict__ s, const float* __restrict__ alpha_eta,
+                                                     PlanArgs a) {
+    const uint32_t k = threadIdx.x;
+    const uint64_t t = s->t;
+    const double alpha = (double)alpha_eta[0], eta = (double)alpha_eta[1];
+    if (k < a.K) {
+        Slot sl;
+        sl.replica = k;
+        sl.gscale = 1.0f;
+        sl.lr = sl.c1 = sl.c2 = sl.beta_mix = 0.0f;
+        sl.mix = draw_u24(a.seed, t, k, a.K) < a.threshold ? 1u : 0u;
+        if (sl.mix) {
+            sl.beta_mix = (float)(alpha * eta / a.p);        // a.p > 0 whenever a draw can fire
+        } else {
+            const uint64_t tau = s->tau[k] + 1;
+            s->tau[k] = tau;
+            const double lr = alpha / (1.0 - a.p);
+            sl.lr = (float)lr;
+            if (a.adamw) {
+                sl.c1 = (float)(lr / (1.0 - pow(a.beta1, (double)tau)));
+                sl.c2 = (float)(1.0 / sqrt(1.0 - pow(a.beta2, (double)tau)));
+            }
+        }
+        s->slot[k] = sl;
+    }
+    __syncthreads();  // every lane has read t
+    if (k == 0) s->t = t + 1;
+}
+
+struct TauArgs {
+    uint64_t tau[PALSGD_MAX_K];
+};
+
+__global__ void schedule_set_kernel(DevSchedule* __restrict__ s, uint64_t t0, TauArgs a) {
+    const uint32_t k = threadIdx.x;
+    if (k < PALSGD_MAX_K) s->tau[k] = a.tau[k];
+    if (k == 0) s->t = t0;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -500,15 +569,6 @@ void set_error(char* dst, const char* fmt, ...) {
     va_end(ap);
 }
 
-// SplitMix64 output function as a counter hash (Steele, Lea, Flood 2014), top 24 bits.
-uint32_t draw_u24(uint64_t seed, uint64_t t, uint32_t k, uint32_t K) {
-    uint64_t z = seed + (t * (uint64_t)K + k + 1ull) * 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return (uint32_t)(z >> 40);
-}
-
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 }  // namespace
@@ -526,6 +586,8 @@ struct palsgd_ctx {
     float* d_scratch = nullptr;    // partial sums of the scalar reductions + their K+2 results
     uint64_t scratch_floats = 0;
     bool clip_armed = false;       // d_scratch holds clipping scales for the next gradient step
+    void* d_schedule = nullptr;    // DevSchedule of the graph-capturable mode
+    bool capturable = false;       // between palsgd_capturable_begin and palsgd_capturable_end
     uint32_t step_waves = 0;       // cap on resident wavefronts per CU, 0 = derive from bytes per wavefront
     uint32_t outer_waves = 0;
     uint32_t outer_variant = 0;
@@ -654,8 +716,8 @@ palsgd_status ensure_scratch(palsgd_ctx* c) {
 }
 
 template <int INNER, int GDT>
-void launch_step(palsgd_ctx* c, const StepArgs& args, uint32_t n_slots, bool any_grad, const float* clip,
-                 hipStream_t st) {
+void launch_step(palsgd_ctx* c, const StepArgs& args, const Slot* dev_slots, uint32_t n_slots, bool any_grad,
+                 const float* clip, hipStream_t st) {
     const uint64_t n = c->P_padded;
     // mixing wavefronts take two tiles each, so a mixing-only launch needs half the grid
     const uint32_t tiles = (uint32_t)(any_grad ? (n + kTile - 1) / kTile : (n + 2 * kTile - 1) / (2 * kTile));
@@ -664,12 +726,25 @@ void launch_step(palsgd_ctx* c, const StepArgs& args, uint32_t n_slots, bool any
     const uint32_t waves = c->step_waves ? c->step_waves : auto_waves(per_elem * kTile);
     dim3 grid(tiles, n_slots), block(kWave);
     Hyper h{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum, c->wd_eff0};
-    if (c->wd_uniform)
-        step_kernel<INNER, GDT, false><<<grid, block, lds_cap(waves, 0), st>>>(
-            args, nullptr, c->buf.X, c->buf.M, c->buf.V, c->buf.G, c->buf.XG, clip, n, c->buf.row_stride, h);
-    else
-        step_kernel<INNER, GDT, true><<<grid, block, lds_cap(waves, 0), st>>>(
-            args, c->d_wd_tab, c->buf.X, c->buf.M, c->buf.V, c->buf.G, c->buf.XG, clip, n, c->buf.row_stride, h);
+    const uint32_t lds = lds_cap(waves, 0);
+    const palsgd_buffers& b = c->buf;
+#define PALSGD_STEP(TAB, DEV, tab)                                                                              \
+    step_kernel<INNER, GDT, TAB, DEV><<<grid, block, lds, st>>>(args, dev_slots, tab, b.X, b.M, b.V, b.G, b.XG, clip, n, \
+                                                                b.row_stride, h)
+    if (c->wd_uniform && !dev_slots) PALSGD_STEP(false, false, nullptr);
+    else if (c->wd_uniform) PALSGD_STEP(false, true, nullptr);
+    else if (!dev_slots) PALSGD_STEP(true, false, c->d_wd_tab);
+    else PALSGD_STEP(true, true, c->d_wd_tab);
+#undef PALSGD_STEP
+}
+
+void dispatch_step(palsgd_ctx* c, const StepArgs& args, const Slot* dev_slots, uint32_t n_slots, bool any_grad,
+                   const float* clip, hipStream_t st) {
+    const bool adamw = c->cfg.inner == PALSGD_INNER_ADAMW, bf16 = c->cfg.grad_dtype == PALSGD_GRAD_BF16;
+    if (adamw && bf16) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16>(c, args, dev_slots, n_slots, any_grad, clip, st);
+    else if (adamw) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_F32>(c, args, dev_slots, n_slots, any_grad, clip, st);
+    else if (bf16) launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_BF16>(c, args, dev_slots, n_slots, any_grad, clip, st);
+    else launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_F32>(c, args, dev_slots, n_slots, any_grad, clip, st);
 }
 
 // Shared body of palsgd_inner_step / palsgd_pseudo_sync / palsgd_step.
@@ -679,6 +754,11 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
     if (!c) {
         set_error(g_error, "%s: NULL context", who);
         return PALSGD_EINVAL;
+    }
+    if (c->capturable) {
+        set_error(c->error, "%s: the schedule is device-resident (palsgd_capturable_begin); use "
+                            "palsgd_step_capturable or call palsgd_capturable_end first", who);
+        return PALSGD_ESTATE;
     }
     if (!(alpha >= 0.0f) || !std::isfinite(alpha)) {
         set_error(c->error, "%s: alpha_t must be finite and >= 0", who);
@@ -733,13 +813,9 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
         if (rc != PALSGD_OK) return rc;
     }
     hipStream_t st = (hipStream_t)stream;
-    const bool adamw = c->cfg.inner == PALSGD_INNER_ADAMW, bf16 = c->cfg.grad_dtype == PALSGD_GRAD_BF16;
     // clipping scales computed by palsgd_clip_grad_norm are consumed by the first gradient step after it
     const float* clip = any_grad && c->clip_armed ? clip_scales(c) : nullptr;
-    if (adamw && bf16) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16>(c, args, n, any_grad, clip, st);
-    else if (adamw) launch_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_F32>(c, args, n, any_grad, clip, st);
-    else if (bf16) launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_BF16>(c, args, n, any_grad, clip, st);
-    else launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_F32>(c, args, n, any_grad, clip, st);
+    dispatch_step(c, args, nullptr, n, any_grad, clip, st);
     palsgd_status rc = check_launch(c, who);
     if (rc != PALSGD_OK) return rc;
     if (clip) c->clip_armed = false;
@@ -923,6 +999,10 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
         set_error(ctx->error, "palsgd_ddp_step: alpha_t must be finite and >= 0");
         return PALSGD_EINVAL;
     }
+    if (ctx->capturable) {
+        set_error(ctx->error, "palsgd_ddp_step: not available while the schedule is device-resident");
+        return PALSGD_ESTATE;
+    }
     const uint32_t K = ctx->cfg.K;
     for (uint32_t k = 1; k < K; ++k)
         if (ctx->tau[k] != ctx->tau[0]) {
@@ -1022,10 +1102,87 @@ palsgd_status palsgd_diagnostics(palsgd_ctx* ctx, float* out_dev, void* stream) 
     return check_launch(ctx, "palsgd_diagnostics");
 }
 
+palsgd_status palsgd_capturable_begin(palsgd_ctx* ctx, uint64_t t0, void* stream) {
+    if (!ctx) {
+        set_error(g_error, "palsgd_capturable_begin: NULL context");
+        return PALSGD_EINVAL;
+    }
+    if (!ctx->d_schedule) {
+        hipError_t e = hipMalloc(&ctx->d_schedule, sizeof(DevSchedule));
+        if (e != hipSuccess) {
+            ctx->d_schedule = nullptr;
+            set_error(ctx->error, "hipMalloc(device schedule): %s", hipGetErrorString(e));
+            return PALSGD_ENOMEM;
+        }
+    }
+    if (!ctx->wd_uniform && !ctx->d_wd_tab) {  // nothing may be allocated once a capture is running
+        palsgd_status rc = build_wd_table(ctx);
+        if (rc != PALSGD_OK) return rc;
+    }
+    (void)lds_per_cu();
+    TauArgs a;
+    for (uint32_t k = 0; k < PALSGD_MAX_K; ++k) a.tau[k] = k < ctx->cfg.K ? ctx->tau[k] : 0;
+    schedule_set_kernel<<<1, kWave, 0, (hipStream_t)stream>>>((DevSchedule*)ctx->d_schedule, t0, a);
+    palsgd_status rc = check_launch(ctx, "palsgd_capturable_begin");
+    if (rc != PALSGD_OK) return rc;
+    ctx->capturable = true;
+    return PALSGD_OK;
+}
+
+palsgd_status palsgd_step_capturable(palsgd_ctx* ctx, const float* alpha_eta_dev, void* stream) {
+    if (!ctx || !alpha_eta_dev) {
+        set_error(ctx ? ctx->error : g_error, "palsgd_step_capturable: NULL argument");
+        return PALSGD_EINVAL;
+    }
+    if (!ctx->capturable) {
+        set_error(ctx->error, "palsgd_step_capturable: call palsgd_capturable_begin first");
+        return PALSGD_ESTATE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    DevSchedule* ds = (DevSchedule*)ctx->d_schedule;
+    PlanArgs a{ctx->cfg.seed, ctx->cfg.p, (double)ctx->cfg.beta1, (double)ctx->cfg.beta2, ctx->cfg.K,
+               ctx->draw_threshold, ctx->cfg.inner == PALSGD_INNER_ADAMW ? 1u : 0u};
+    plan_kernel<<<1, kWave, 0, st>>>(ds, alpha_eta_dev, a);
+    StepArgs none;
+    memset(&none, 0, sizeof none);
+    const float* clip = ctx->clip_armed ? clip_scales(ctx) : nullptr;
+    dispatch_step(ctx, none, ds->slot, ctx->cfg.K, true, clip, st);
+    palsgd_status rc = check_launch(ctx, "palsgd_step_capturable");
+    if (rc != PALSGD_OK) return rc;
+    if (clip) ctx->clip_armed = false;
+    return PALSGD_OK;
+}
+
+palsgd_status palsgd_capturable_end(palsgd_ctx* ctx, uint64_t* t_out, void* stream) {
+    if (!ctx) {
+        set_error(g_error, "palsgd_capturable_end: NULL context");
+        return PALSGD_EINVAL;
+    }
+    if (!ctx->capturable) {
+        set_error(ctx->error, "palsgd_capturable_end: not in capturable mode");
+        return PALSGD_ESTATE;
+    }
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    uint64_t host[1 + PALSGD_MAX_K];
+    if (e == hipSuccess) e = hipMemcpy(host, ctx->d_schedule, sizeof host, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) {
+        set_error(ctx->error, "palsgd_capturable_end: %s", hipGetErrorString(e));
+        return PALSGD_EHIP;
+    }
+    for (uint32_t k = 0; k < ctx->cfg.K; ++k) ctx->tau[k] = host[1 + k];
+    if (t_out) *t_out = host[0];
+    ctx->capturable = false;
+    return PALSGD_OK;
+}
+
 palsgd_status palsgd_get_state(const palsgd_ctx* ctx, uint64_t* tau, uint64_t* n_outer) {
     if (!ctx) {
         set_error(g_error, "palsgd_get_state: NULL context");
         return PALSGD_EINVAL;
+    }
+    if (ctx->capturable) {
+        set_error(g_error, "palsgd_get_state: the step counts are on the device; call palsgd_capturable_end first");
+        return PALSGD_ESTATE;
     }
     if (tau) memcpy(tau, ctx->tau, ctx->cfg.K * sizeof(uint64_t));
     if (n_outer) *n_outer = ctx->n_outer;
@@ -1036,6 +1193,10 @@ palsgd_status palsgd_set_state(palsgd_ctx* ctx, const uint64_t* tau, uint64_t n_
     if (!ctx || !tau) {
         set_error(ctx ? ctx->error : g_error, "palsgd_set_state: NULL argument");
         return PALSGD_EINVAL;
+    }
+    if (ctx->capturable) {
+        set_error(ctx->error, "palsgd_set_state: the step counts are on the device; call palsgd_capturable_end first");
+        return PALSGD_ESTATE;
     }
     memcpy(ctx->tau, tau, ctx->cfg.K * sizeof(uint64_t));
     ctx->n_outer = n_outer;
@@ -1048,6 +1209,7 @@ void palsgd_destroy(palsgd_ctx* ctx) {
     if (!ctx) return;
     if (ctx->d_wd_tab) (void)hipFree(ctx->d_wd_tab);
     if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
+    if (ctx->d_schedule) (void)hipFree(ctx->d_schedule);
     delete ctx;
 }
 
