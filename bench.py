@@ -204,12 +204,14 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     return res
 
 
-def run_cpu_baseline(w, slice_div=2):
+def run_cpu_baseline(w, slice_div=2, threads=None):
     """The oracle, as it stands, on the first 1/slice_div of every replica row for H+1 steps."""
     import oracle
     from paper_2504_18454_amd.workloads import flat_layout, to_bf16_bits
 
-    threads = max(1, min(int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1), os.cpu_count() or 1))
+    if threads is None:
+        threads = max(1, min(int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1),
+                             os.cpu_count() or 1))
     oracle.set_threads(threads)
     offs, row = flat_layout(w.numels)
     n = max(64, row // slice_div // 64 * 64)
@@ -255,7 +257,11 @@ def main():
     from paper_2504_18454_amd.workloads import workload
     w = workload(a.workload)
     r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph)
-    cpu = None if a.no_cpu_baseline else run_cpu_baseline(w)
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = run_cpu_baseline(w)
+        one = run_cpu_baseline(w, slice_div=64, threads=1)       # the same loop on one core, smaller slice
+        cpu["one_core"] = {"value": one["value"], "sample": one["sample"]}
     gb = grad_bytes_per_elem(w.inner, w.grad_dtype)
     out = {
         "metric": "replica-param updates/s", "value": r["updates"] / r["elapsed"], "unit": "replica-param updates/s",

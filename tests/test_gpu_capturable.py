@@ -96,3 +96,25 @@ def test_replayed_graph_of_a_window_follows_alg1(grad_dtype):
     tau, _ = r.lib.palsgd_get_state()
     assert tau == [int(v) for v in r.ora.tau]
     r.close()
+
+
+def test_config_gptneo125m_k8_device_schedule_sampled():
+    """The benchmark configuration through the device-resident schedule: K=8, GPT-Neo-125M shapes, bf16 gradients,
+    p=0.05, H=64, 130 steps (two outer steps), full-size buffers, oracle on sampled positions."""
+    from paper_2504_18454_amd.workloads import workload
+    w = workload("gptneo125m_k8")
+    r = _run(K=w.K, numels=w.numels, inner=w.inner, grad_dtype=w.grad_dtype, p=w.p, H=w.H, alpha=w.alpha, eta=w.eta,
+             sigma=w.sigma, seed=w.seed, per_edge=256, n_random=1 << 16)
+    ae = torch.tensor([r.alpha, r.eta], dtype=torch.float32, device="cuda:0")
+    r.lib.palsgd_capturable_begin(0)
+    for _ in range(130):
+        t = r.t
+        r.make_gradients()
+        _, synced = r.ora.iteration(t, r.alpha, r.eta)
+        r.lib.palsgd_step_capturable(ae)
+        if synced:
+            r.lib.palsgd_outer_step(t)
+        r.t += 1
+    assert r.lib.palsgd_capturable_end() == 130
+    print("worst err/bound", r.compare())
+    r.close()

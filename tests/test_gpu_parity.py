@@ -158,11 +158,11 @@ def test_config_smallcnn_k64_sampled():
 
 
 def test_config_gptneo1p3b_k8_sampled():
-    """K=8, GPT-Neo-1.3B shapes: 10.5 G replica-elements, about 158 GB resident; H+2 steps cover one outer step."""
+    """K=8, GPT-Neo-1.3B shapes: 10.5 G replica-elements, about 158 GB resident; 128 steps = two windows of H."""
     free, total = torch.cuda.mem_get_info()
     if free < 200 * 2 ** 30:
         pytest.skip("needs about 200 GB of free device memory")
-    _sampled("gptneo1p3b_k8", steps=66, per_edge=256, n_random=1 << 16)
+    _sampled("gptneo1p3b_k8", steps=128, per_edge=256, n_random=1 << 16)
 
 
 def test_deterministic_and_stream_independent():
