@@ -15,12 +15,19 @@
 //     which nothing is used): about 72 KiB of loads+stores in flight per CU is the
 //     measured optimum; full occupancy loses 10-15 % to DRAM page conflicts.
 //
-//   step_kernel   Alg. 1 local update of all K workers in one launch: a wavefront owns
-//                 (tile of a row, worker); the worker's branch (gradient step / mixing
-//                 step) is uniform over the wavefront, so there is no divergence.
-//   outer_kernel  Alg. 1 outer step: K-way mean over the replica rows, Delta,
-//                 OuterOPT with (Nesterov) momentum, restart of the K workers.
-//   init_kernel   x_k^(0) <- x^(0), cleared optimizer state.
+//   step_kernel    Alg. 1 local update of all K workers in one launch: a wavefront owns
+//                  (tile of a row, worker); the worker's branch (gradient step / mixing
+//                  step) is uniform over the wavefront, so there is no divergence.
+//   outer_kernel_* Alg. 1 outer step: K-way mean of the differences x - x_k, OuterOPT with
+//                  (Nesterov) momentum, restart of the K workers; optionally the
+//                  consensus-distance diagnostics from the values already in registers.
+//   init_kernel    x_k^(0) <- x^(0), cleared optimizer state.
+//   ddp_kernel     DDP step of the warm-up phase: K-way gradient mean + one InnerOPT step.
+//   plan_kernel    device-resident schedule (draws, step counts, bias corrections) for
+//                  callers that replay the step from a HIP graph.
+//   sumsq_kernel, diag_kernel, fold_kernel, *_finish_kernel
+//                  scalar reductions (gradient norms for clipping, consensus distance):
+//                  lane-local sums, a shuffle tree per wavefront, fixed-order folds in double.
 //
 // No matrix cores: nothing here is a contraction.  No data goes through LDS in the step
 // kernel: there is no reuse to stage.  Each XCD's private L2 is irrelevant to pure
@@ -565,6 +572,8 @@ __global__ __launch_bounds__(kThreads) void diag_finish_kernel(const double* __r
     }
 }
 
+// ======== host side: context, argument checks, launches ========
+
 thread_local char g_error[256] = "";
 
 void set_error(char* dst, const char* fmt, ...) {
@@ -589,7 +598,6 @@ struct palsgd_ctx {
     float wd_eff0 = 0.0f;          // weight_decay * that multiplier
     float* d_wd_tab = nullptr;     // else: weight_decay * multiplier per 64 elements of a row
     float* d_scratch = nullptr;    // partial sums of the scalar reductions + their K+2 results
-    uint64_t scratch_floats = 0;
     bool clip_armed = false;       // d_scratch holds clipping scales for the next gradient step
     void* d_schedule = nullptr;    // DevSchedule of the graph-capturable mode
     bool capturable = false;       // between palsgd_capturable_begin and palsgd_capturable_end
@@ -716,7 +724,6 @@ palsgd_status ensure_scratch(palsgd_ctx* c) {
         return PALSGD_ENOMEM;
     }
     c->d_scratch = d;
-    c->scratch_floats = floats;
     return PALSGD_OK;
 }
 

@@ -1,5 +1,4 @@
 """CPU checks of bench.py's contract pieces that need no GPU."""
-import hashlib
 import os
 import subprocess
 import sys
@@ -18,8 +17,7 @@ def test_algorithmic_bytes_and_traffic_key():
     assert bench.grad_bytes_per_elem("adamw", "bf16") == 26 and bench.grad_bytes_per_elem("adamw", "f32") == 28
     assert bench.grad_bytes_per_elem("sgdm", "f32") == 20 and bench.grad_bytes_per_elem("sgdm", "bf16") == 18
     # the counter-derived traffic is reported only for the kernel source it was measured with
-    src = os.path.join(ROOT, "paper_2504_18454_amd", "csrc", "palsgd.hip")
-    same = hashlib.sha256(open(src, "rb").read()).hexdigest() == bench.TRAFFIC["kernel_source_sha256"]
+    same = bench.kernel_source_digest() == bench.TRAFFIC["kernel_source_sha256"]
     got = bench.measured_traffic("gptneo125m_k8")
     assert (got == bench.TRAFFIC["bytes_per_launch"]) if same else (got is None)
     assert bench.measured_traffic("resnet50_k8") is None
