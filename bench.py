@@ -205,6 +205,13 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
         res["clip_grad_norm"] = dict(ms=ms, gbps=float(P) * K * gB / ms / 1e6, bytes_per_elem=K * gB)
         ms = timed(lambda: ctx.palsgd_diagnostics(out2, stream))
         res["diagnostics"] = dict(ms=ms, gbps=float(P) * (4 * K + 4) / ms / 1e6, bytes_per_elem=4 * K + 4)
+        ones, zeros = np.ones(K, np.uint8), np.zeros(K, np.uint8)
+        gb_ = grad_bytes_per_elem(w.inner, w.grad_dtype)
+        ms = timed(lambda: ctx.palsgd_inner_step(0, w.alpha, None, zeros, stream))
+        res["gradient_branch_only"] = dict(ms=ms, gbps=float(P) * K * gb_ / ms / 1e6, bytes_per_elem=gb_)
+        if w.p > 0:
+            ms = timed(lambda: ctx.palsgd_pseudo_sync(0, w.alpha, w.eta, ones, stream))
+            res["mixing_branch_only"] = dict(ms=ms, gbps=float(P) * K * 12 / ms / 1e6, bytes_per_elem=12)
         ctx.palsgd_outer_step(0, stream)                # workers identical again, as the DDP step requires
         tau0 = max(ctx.palsgd_get_state()[0])
         ctx.palsgd_set_state([tau0] * K, ctx.palsgd_get_state()[1])
@@ -295,7 +302,8 @@ def main():
     if a.graph:
         out["hip_graph_replay"] = r["graph"]
     if a.extra_kernels:
-        out["extra_kernels"] = {k: r[k] for k in ("ddp_step", "clip_grad_norm", "diagnostics")}
+        out["extra_kernels"] = {k: r[k] for k in ("gradient_branch_only", "mixing_branch_only", "ddp_step",
+                                                  "clip_grad_norm", "diagnostics") if k in r}
     print(json.dumps(out))
 
 
