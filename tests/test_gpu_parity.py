@@ -238,3 +238,39 @@ def test_step_loop_is_capturable_in_a_hip_graph():
             assert torch.equal(got, want), f"replay {i}"
         scratch = torch.randn(1 << 20, device="cuda:0").sum().item()   # eager work between replays
     a.close(); b.close()
+
+
+def test_non_finite_gradients_stay_where_they_are():
+    """The hot path does not check gradients: a NaN or Inf in g_k poisons exactly that element of that replica
+    (and, through the K-way mean, that element of the global model at the next synchronisation); every other
+    element matches the oracle as usual."""
+    r = _run(K=3, numels=[3000, 64, 500], inner="adamw", p=0.0, H=2, seed=24, sigma=0.05)
+    bad = [(0, 5, float("nan")), (1, 3000 + 64 - 1 + 1, float("inf")), (2, 100, float("-inf"))]   # (replica, position, value)
+    r.make_gradients()
+    for k, i, v in bad:
+        r.G[k, i] = v
+        r.ora.G[k, i] = v
+    r.ora.iteration(0, r.alpha, r.eta)
+    r.lib.palsgd_step(0, r.alpha, r.eta)
+    torch.cuda.synchronize()
+    X = r.X.cpu().numpy()
+    for k, i, _ in bad:
+        assert np.isnan(X[k, i]) and np.isnan(r.ora.X[k, i])
+    mask = np.ones_like(X, bool)
+    for k, i, _ in bad:
+        mask[k, i] = False
+    assert np.isfinite(X[mask]).all()
+    np.testing.assert_allclose(X[mask], r.ora.X[mask], rtol=1e-5, atol=1e-7)
+    # next step synchronises: the poisoned columns of the global model become NaN on both sides, nothing else
+    r.make_gradients()
+    r.ora.iteration(1, r.alpha, r.eta)
+    r.lib.palsgd_step(1, r.alpha, r.eta)
+    r.lib.palsgd_outer_step(1)
+    torch.cuda.synchronize()
+    XG = r.XG.cpu().numpy()
+    cols = sorted({i for _, i, _ in bad})
+    assert np.isnan(XG[cols]).all() and np.isnan(r.ora.XG[cols]).all()
+    ok = np.ones(XG.size, bool); ok[cols] = False
+    assert np.isfinite(XG[ok]).all()
+    np.testing.assert_allclose(XG[ok], r.ora.XG[ok], rtol=1e-5, atol=1e-7)
+    r.close()

@@ -126,3 +126,30 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libpalsgd.so")
     with pytest.raises(ImportError):
         binding.lib()
+
+
+def test_binding_structs_match_the_header_layout(tmp_path):
+    """The ctypes mirrors of palsgd_config / palsgd_buffers have the header's size and field offsets
+    (checked by compiling the header with the host C compiler)."""
+    import subprocess
+    fields_cfg = [f[0] for f in binding.Config._fields_]
+    fields_buf = [f[0] for f in binding.Buffers._fields_]
+    src = tmp_path / "layout.c"
+    lines = ['#include <stdio.h>', '#include <stddef.h>', f'#include "{HEADER}"', 'int main(void){',
+             'printf("%zu\\n", sizeof(palsgd_config));']
+    lines += [f'printf("%zu\\n", offsetof(palsgd_config, {f}));' for f in fields_cfg]
+    lines += ['printf("%zu\\n", sizeof(palsgd_buffers));']
+    lines += [f'printf("%zu\\n", offsetof(palsgd_buffers, {f}));' for f in fields_buf]
+    lines += ['printf("%d %d %d %d %d\\n", PALSGD_OK, PALSGD_EINVAL, PALSGD_ENOMEM, PALSGD_EHIP, PALSGD_ESTATE);',
+              'printf("%u\\n", PALSGD_MAX_K);', 'return 0;}']
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-Werror", "-o", str(exe), str(src)])
+    out = subprocess.check_output([str(exe)], text=True).split("\n")
+    want = [C.sizeof(binding.Config)] + [getattr(binding.Config, f).offset for f in fields_cfg]
+    want += [C.sizeof(binding.Buffers)] + [getattr(binding.Buffers, f).offset for f in fields_buf]
+    got = [int(v) for v in out[:len(want)]]
+    assert got == want
+    assert out[len(want)].split() == ["0", "1", "2", "3", "4"]
+    assert (binding.PALSGD_OK, binding.PALSGD_EINVAL, binding.PALSGD_ENOMEM, binding.PALSGD_EHIP, binding.PALSGD_ESTATE) == (0, 1, 2, 3, 4)
+    assert int(out[len(want) + 1]) == binding.MAX_K
