@@ -280,6 +280,7 @@ def main():
         cpu = run_cpu_baseline(w)
         one = run_cpu_baseline(w, slice_div=64, threads=1)       # the same loop on one core, smaller slice
         cpu["one_core"] = {"value": one["value"], "sample": one["sample"]}
+        cpu["gpu_over_cpu"] = r["updates"] / r["elapsed"] / cpu["value"]       # context only: the roofline fraction is the measure
     gb = grad_bytes_per_elem(w.inner, w.grad_dtype)
     out = {
         "metric": "replica-param updates/s", "value": r["updates"] / r["elapsed"], "unit": "replica-param updates/s",
