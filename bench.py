@@ -215,7 +215,7 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
         ctx.palsgd_outer_step(0, stream)                # workers identical again, as the DDP step requires
         tau0 = max(ctx.palsgd_get_state()[0])
         ctx.palsgd_set_state([tau0] * K, ctx.palsgd_get_state()[1])
-        ddp_b = K * gB + state + 4 + K * state         # read K gradients + x, m(, v); write XG + K rows of x, m(, v)
+        ddp_b = K * gB + state + 4 + 4 * K + (state - 4)  # read K gradients + x, m(, v); write XG, K rows of x, one of m(, v)
         ms = timed(lambda: ctx.palsgd_ddp_step(0, w.alpha, None, stream))
         res["ddp_step"] = dict(ms=ms, gbps=float(P) * ddp_b / ms / 1e6, bytes_per_elem=ddp_b)
     ctx.palsgd_destroy()

@@ -141,12 +141,19 @@ palsgd_status palsgd_outer_step_diag(palsgd_ctx *ctx, uint64_t t, float *diag_ou
  * gradient at every step before the optimizer update; Sec. 4.3, Sec. 5.1):
  * gbar = (1/K) sum_k grad_scale[k] G[k];  x <- InnerOPT(x, gbar, alpha_t) (no 1/(1-p)
  * rescale: there is no mixing branch);  the result is stored to XG and to every row of X,
- * the InnerOPT state to every row of M, V, and every worker's step count advances.
+ * and every worker's step count advances.  The InnerOPT state of the identical workers
+ * is kept once, in worker 0's rows of M, V; rows 1..K-1 are stale during the warm-up and
+ * are filled from row 0 by the first palsgd_inner_step / palsgd_step /
+ * palsgd_capturable_begin that follows, or by palsgd_ddp_finish.
  * Precondition: all workers are identical (true from palsgd_init through the warm-up);
  * the common model is read from XG, the common InnerOPT state from worker 0.  ESTATE if
  * the workers' step counts differ.  OM is not touched.  Clipping scales left by
  * palsgd_clip_grad_norm are not consumed here. */
 palsgd_status palsgd_ddp_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, const float *grad_scale, void *stream);
+
+/* End of the warm-up made explicit: copies worker 0's InnerOPT state into rows 1..K-1 of
+ * M, V if DDP steps left them stale; no launch otherwise. */
+palsgd_status palsgd_ddp_finish(palsgd_ctx *ctx, void *stream);
 
 /* Gradient clipping by the global L2 norm of each worker's gradient (App. B says the GPT-Neo runs
  * clip gradients; the paper prints no threshold): norm_k = |G[k]|_2 and

@@ -398,7 +398,8 @@ __global__ void schedule_set_kernel(DevSchedule* __restrict__ s, uint64_t t0, Ta
 // DDP step of the warm-up phase (Sec. 3.1: All-Reduce of the gradient, then the optimizer
 // update, identical on every worker; Sec. 4.3).  One wavefront per tile: weighted mean of the
 // K gradient rows (k ascending, eight loads in flight), InnerOPT on the common model (read
-// from XG) with the common state (read from replica 0), result stored to XG and all K rows.
+// from XG) with the common state (replica 0's), model stored to XG and all K rows of X, state
+// to replica 0 only: the other replicas' copies are made once, when the warm-up ends.
 struct DdpArgs {
     float w[PALSGD_MAX_K];  // grad_scale[k]
     float inv_k, lr, c1, c2;
@@ -432,11 +433,23 @@ __global__ __launch_bounds__(kWave) void ddp_kernel(const DdpArgs a, const float
     else
         sgdm4(xv, mv, g, h.momentum, a.lr, wd);
     st4(XG + e, xv);
-    for (uint32_t k = 0; k < K; ++k) {
+    st4(M + e, mv);  // the common InnerOPT state lives in replica 0 during the warm-up
+    if (INNER == PALSGD_INNER_ADAMW) st4(V + e, vv);
+    for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xv);
+}
+
+// End of the warm-up: replicas 1..K-1 take over the common InnerOPT state of replica 0.
+__global__ __launch_bounds__(kWave) void moments_broadcast_kernel(float* __restrict__ M, float* __restrict__ V,
+                                                                  uint64_t n, uint64_t row_stride, uint32_t K) {
+    const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
+    if (e >= n) return;
+    const f4 mv = ld4(M + e);
+    f4 vv;
+    if (V) vv = ld4(V + e);
+    for (uint32_t k = 1; k < K; ++k) {
         const uint64_t o = (uint64_t)k * row_stride + e;
-        st4(X + o, xv);
         st4(M + o, mv);
-        if (INNER == PALSGD_INNER_ADAMW) st4(V + o, vv);
+        if (V) st4(V + o, vv);
     }
 }
 
@@ -599,6 +612,7 @@ struct palsgd_ctx {
     float* d_wd_tab = nullptr;     // else: weight_decay * multiplier per 64 elements of a row
     float* d_scratch = nullptr;    // partial sums of the scalar reductions + their K+2 results
     bool clip_armed = false;       // d_scratch holds clipping scales for the next gradient step
+    bool moments_shared = false;   // after DDP steps: only replica 0's M, V are current
     void* d_schedule = nullptr;    // DevSchedule of the graph-capturable mode
     bool capturable = false;       // between palsgd_capturable_begin and palsgd_capturable_end
     uint32_t step_waves = 0;       // cap on resident wavefronts per CU, 0 = derive from bytes per wavefront
@@ -750,6 +764,21 @@ void launch_step(palsgd_ctx* c, const StepArgs& args, const Slot* dev_slots, uin
 #undef PALSGD_STEP
 }
 
+// Replicas 1..K-1 get replica 0's InnerOPT state if DDP steps left it shared.
+palsgd_status unshare_moments(palsgd_ctx* c, const char* who, hipStream_t st) {
+    if (!c->moments_shared) return PALSGD_OK;
+    if (c->cfg.K > 1) {
+        const uint32_t bytes = (c->cfg.inner == PALSGD_INNER_ADAMW ? 8u : 4u) * c->cfg.K * kTile;
+        float* v = c->cfg.inner == PALSGD_INNER_ADAMW ? c->buf.V : nullptr;
+        moments_broadcast_kernel<<<tile_count(c), kWave, lds_cap(auto_waves(bytes, 4), 0), st>>>(
+            c->buf.M, v, c->P_padded, c->buf.row_stride, c->cfg.K);
+        palsgd_status rc = check_launch(c, who);
+        if (rc != PALSGD_OK) return rc;
+    }
+    c->moments_shared = false;
+    return PALSGD_OK;
+}
+
 void dispatch_step(palsgd_ctx* c, const StepArgs& args, const Slot* dev_slots, uint32_t n_slots, bool any_grad,
                    const float* clip, hipStream_t st) {
     const bool adamw = c->cfg.inner == PALSGD_INNER_ADAMW, bf16 = c->cfg.grad_dtype == PALSGD_GRAD_BF16;
@@ -825,6 +854,10 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
         if (rc != PALSGD_OK) return rc;
     }
     hipStream_t st = (hipStream_t)stream;
+    if (any_grad) {
+        palsgd_status rc = unshare_moments(c, who, st);
+        if (rc != PALSGD_OK) return rc;
+    }
     // clipping scales computed by palsgd_clip_grad_norm are consumed by the first gradient step after it
     const float* clip = any_grad && c->clip_armed ? clip_scales(c) : nullptr;
     dispatch_step(c, args, nullptr, n, any_grad, clip, st);
@@ -1048,7 +1081,7 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
     }
     const uint64_t n = ctx->P_padded;
     const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
-    const uint32_t per_elem = (adamw ? 12u + 12u * K : 8u + 8u * K) + 4u + K * (bf16 ? 2u : 4u);
+    const uint32_t per_elem = (adamw ? 24u : 16u) + 4u * K + K * (bf16 ? 2u : 4u);
     const uint32_t lds = lds_cap(ctx->outer_waves ? ctx->outer_waves : auto_waves(per_elem * kTile, 4), 0);
     Hyper h{ctx->cfg.beta1, ctx->cfg.beta2, ctx->cfg.eps, ctx->cfg.momentum, ctx->wd_eff0};
     hipStream_t st = (hipStream_t)stream;
@@ -1066,7 +1099,16 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
     palsgd_status rc = check_launch(ctx, "palsgd_ddp_step");
     if (rc != PALSGD_OK) return rc;
     for (uint32_t k = 0; k < K; ++k) ctx->tau[k] += 1;
+    ctx->moments_shared = true;
     return PALSGD_OK;
+}
+
+palsgd_status palsgd_ddp_finish(palsgd_ctx* ctx, void* stream) {
+    if (!ctx) {
+        set_error(g_error, "palsgd_ddp_finish: NULL context");
+        return PALSGD_EINVAL;
+    }
+    return unshare_moments(ctx, "palsgd_ddp_finish", (hipStream_t)stream);
 }
 
 palsgd_status palsgd_clip_grad_norm(palsgd_ctx* ctx, float max_norm, float* norms_out_dev, void* stream) {
@@ -1132,6 +1174,10 @@ palsgd_status palsgd_capturable_begin(palsgd_ctx* ctx, uint64_t t0, void* stream
         if (rc != PALSGD_OK) return rc;
     }
     (void)lds_per_cu();
+    {
+        palsgd_status rc = unshare_moments(ctx, "palsgd_capturable_begin", (hipStream_t)stream);
+        if (rc != PALSGD_OK) return rc;
+    }
     TauArgs a;
     for (uint32_t k = 0; k < PALSGD_MAX_K; ++k) a.tau[k] = k < ctx->cfg.K ? ctx->tau[k] : 0;
     schedule_set_kernel<<<1, kWave, 0, (hipStream_t)stream>>>((DevSchedule*)ctx->d_schedule, t0, a);

@@ -24,11 +24,37 @@ def test_ddp_warmup_then_palsgd(inner, grad_dtype, K):
              wd_mult=[1, 0, 1, 1, 0.5, 1, 0], row_extra=1)
     gs = None if K != 3 else [1.0, 0.5, 2.0]
     r.ddp_iterate(5, grad_scale=gs)
-    r.compare()
-    for k in range(K):                                  # all workers identical after DDP steps
-        assert torch.equal(r.X[k], r.XG) and torch.equal(r.M[k], r.M[0])
+    explicit = K % 2 == 1
+    if explicit:                                        # the common InnerOPT state is copied to every worker on request ...
+        r.lib.palsgd_ddp_finish()
+        r.compare()
+        for k in range(K):
+            assert torch.equal(r.X[k], r.XG) and torch.equal(r.M[k], r.M[0])
+        r.lib.palsgd_ddp_finish()                       # a second call has nothing to do
+    else:                                               # ... or by the first PALSGD step that needs it
+        torch.cuda.synchronize()
+        for k in range(K):
+            assert torch.equal(r.X[k], r.XG)
     assert r.lib.palsgd_get_state()[0] == [5] * K
     r.iterate(7)                                        # the PALSGD phase continues from the warm-up state
+    r.compare()
+    r.close()
+
+
+def test_ddp_then_device_schedule():
+    r = _run(K=4, numels=RAGGED, grad_dtype="bf16", p=0.25, H=3, seed=36, sigma=0.05)
+    r.ddp_iterate(4)
+    ae = torch.tensor([r.alpha, r.eta], dtype=torch.float32, device="cuda:0")
+    r.lib.palsgd_capturable_begin(r.t)                  # also ends the warm-up's shared InnerOPT state
+    for _ in range(5):
+        t = r.t
+        r.make_gradients()
+        _, synced = r.ora.iteration(t, r.alpha, r.eta)
+        r.lib.palsgd_step_capturable(ae)
+        if synced:
+            r.lib.palsgd_outer_step(t)
+        r.t += 1
+    assert r.lib.palsgd_capturable_end() == r.t
     r.compare()
     r.close()
 
@@ -133,6 +159,7 @@ def test_config_gptneo125m_k8_ddp_sampled():
     r = _run(K=w.K, numels=w.numels, inner=w.inner, grad_dtype=w.grad_dtype, p=w.p, H=w.H, alpha=w.alpha, eta=w.eta,
              sigma=w.sigma, seed=w.seed, per_edge=256, n_random=1 << 16)
     r.ddp_iterate(16)
+    r.lib.palsgd_ddp_finish()
     r.compare()
     r.iterate(70)
     print("worst err/bound", r.compare())
