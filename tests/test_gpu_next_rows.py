@@ -164,3 +164,14 @@ def test_config_gptneo125m_k8_ddp_sampled():
     r.iterate(70)
     print("worst err/bound", r.compare())
     r.close()
+
+
+def test_worked_example_converges():
+    """The example loop (DDP warm-up, clipping, PALSGD, diagnostics) drives the global model to the minimiser;
+    the consensus distance is positive before each synchronisation and exactly zero after the last one."""
+    from paper_2504_18454_amd.example_quadratic import run
+    history, after = run(verbose=False)
+    errs = [h[1] for h in history]
+    assert errs[-1] < 0.05 and errs[-1] < errs[0]
+    assert all(h[2] > 0 and h[3] > 0 for h in history)
+    assert after == [0.0, 0.0]
