@@ -327,3 +327,23 @@ def test_theorem_parameters_contract_on_quadratic(oracle_mod):
         return np.linalg.norm(st.XG - c) / d0
     e2, e16 = run(2, 5), run(16, 5)
     assert e2 < 0.1 and e16 < e2
+
+
+def test_results_do_not_depend_on_the_thread_count(oracle_mod):
+    """The element loops are split statically over threads; no arithmetic crosses elements, so any thread
+    count gives the same bits."""
+    def run(threads):
+        oracle_mod.set_threads(threads)
+        rng = np.random.default_rng(28)
+        numels = [5000, 3, 777]
+        st = _state(oracle_mod, 3, _padded(rng, numels), numels, inner="adamw", grad_dtype="f32", p=0.3, H=3)
+        for t in range(7):
+            st.G[...] = np.stack([_padded(rng, numels) for _ in range(3)])
+            st.iteration(t, 1e-3, 16.0)
+        return st.X.copy(), st.M.copy(), st.V.copy(), st.XG.copy(), st.OM.copy()
+    try:
+        a, b = run(1), run(7)
+    finally:
+        oracle_mod.set_threads(min(8, __import__("os").cpu_count() or 1))
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
