@@ -38,6 +38,8 @@ def _load():
         _lib.ora_ddp_step.argtypes = [C.c_void_p, C.c_double, C.c_void_p]
         _lib.ora_grad_norm.restype = C.c_double
         _lib.ora_grad_norm.argtypes = [C.c_void_p, C.c_int, C.c_uint64]
+        _lib.ora_mean_grad_norm.restype = C.c_double
+        _lib.ora_mean_grad_norm.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_uint32, C.c_uint64, C.c_void_p]
         _lib.ora_clip_scale.restype = C.c_double
         _lib.ora_clip_scale.argtypes = [C.c_double, C.c_double]
         _lib.ora_diagnostics.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p]
@@ -104,6 +106,15 @@ def outer(X, xg, om, lr_o, mu_o, nesterov):
 def grad_norm(g):
     gp, gd = _gptr(g)
     return float(_load().ora_grad_norm(gp, gd, g.size))
+
+
+def mean_grad_norm(G, grad_scale=None):
+    """Norm of (1/K) sum_k grad_scale_k G[k] for G [K, row]."""
+    gp, gd = _gptr(G)
+    K, row = G.shape
+    gs = None if grad_scale is None else np.ascontiguousarray(grad_scale, dtype=np.float64)
+    gsp = None if gs is None else gs.ctypes.data_as(C.c_void_p)
+    return float(_load().ora_mean_grad_norm(gp, gd, row, K, row, gsp))
 
 
 def clip_scale(norm, max_norm):
@@ -207,6 +218,9 @@ class OracleState:
     def ddp_step(self, alpha_t, grad_scale=None):
         gs, gsp = self._opt(grad_scale, np.float64)
         self.lib.ora_ddp_step(C.byref(self.s), float(np.float32(alpha_t)), gsp)
+
+    def mean_grad_norm(self, grad_scale=None):
+        return mean_grad_norm(self.G, grad_scale)
 
     def grad_norms(self):
         return np.array([grad_norm(self.G[k]) for k in range(self.K)])

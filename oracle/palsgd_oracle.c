@@ -369,6 +369,26 @@ double ora_grad_norm(const void *g, int g_dtype, uint64_t n)
     return sqrt(sum);
 }
 
+/* Norm of the averaged gradient, for clipping in the DDP phase (there the     */
+/* gradients are averaged before the optimizer sees them, Sec. 3.1, so the    */
+/* norm that is clipped is that of gbar = (1/K) sum_k grad_scale_k g_k).       */
+double ora_mean_grad_norm(const void *G, int g_dtype, uint64_t row_stride, uint32_t K, uint64_t n,
+                          const double *grad_scale)
+{
+    size_t gbytes = g_dtype == 0 ? 4 : 2;
+    double sum = 0.0;
+    for (uint64_t i = 0; i < n; ++i) {
+        double gbar = 0.0;
+        for (uint32_t k = 0; k < K; ++k) {
+            const void *gk = (const char *)G + (uint64_t)k * row_stride * gbytes;
+            gbar += (grad_scale ? grad_scale[k] : 1.0) * grad_at(gk, g_dtype, i);
+        }
+        gbar /= (double)K;
+        sum += gbar * gbar;
+    }
+    return sqrt(sum);
+}
+
 double ora_clip_scale(double norm, double max_norm)
 {
     double c = max_norm / (norm + 1e-6);

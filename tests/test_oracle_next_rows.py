@@ -150,3 +150,23 @@ def test_consensus_distance_is_zero_after_sync(oracle_mod):
         _, synced = st.iteration(t, 1e-3, 16.0)
         xi, d2 = st.diagnostics()
         assert (xi == 0.0 and d2 == 0.0) if synced else xi > 0.0
+
+
+def test_mean_gradient_norm_matches_library_and_single_worker(oracle_mod):
+    rng = np.random.default_rng(46)
+    K, n = 5, 3001
+    G = rng.standard_normal((K, n)).astype(f32)
+    gs = np.array([1.0, 0.5, 2.0, 0.0, 1.5])
+    want = np.linalg.norm((gs[:, None] * G.astype(np.float64)).sum(axis=0) / K)
+    assert oracle_mod.mean_grad_norm(G, gs) == pytest.approx(want, rel=1e-13)
+    assert oracle_mod.mean_grad_norm(G) == pytest.approx(np.linalg.norm(G.astype(np.float64).mean(axis=0)), rel=1e-13)
+    # one worker: the norm of the mean is the norm of its gradient; clipping the mean = the library's clip on it
+    assert oracle_mod.mean_grad_norm(G[:1]) == pytest.approx(oracle_mod.grad_norm(G[0]), rel=1e-14)
+    p = torch.nn.Parameter(torch.zeros(n, dtype=torch.float64))
+    p.grad = torch.tensor(G.astype(np.float64).mean(axis=0))
+    torch.nn.utils.clip_grad_norm_([p], 0.3)
+    scale = oracle_mod.clip_scale(oracle_mod.mean_grad_norm(G), 0.3)
+    np.testing.assert_allclose(p.grad.numpy(), scale * G.astype(np.float64).mean(axis=0), rtol=1e-13)
+    gb = to_bf16_bits(G)
+    assert oracle_mod.mean_grad_norm(gb) == pytest.approx(
+        np.linalg.norm(from_bf16_bits(gb).astype(np.float64).mean(axis=0)), rel=1e-13)
