@@ -32,23 +32,24 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per launch of step_kernel from two rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE, each scaled by
 # what it reads for the 1 GiB set-up copy); summary in profiles/gptneo125m_k8_hbm_counters.txt.  The figure
-# holds for one kernel source only: it is reported as null as soon as the device code of csrc/palsgd.hip
-# (comments and white space aside) differs from the file the counters were taken with.
+# holds for one kernel source only: it is reported as null as soon as the code of step_kernel and its helpers
+# in csrc/palsgd.hip (comments and white space aside) differs from the file the counters were taken with.
 TRAFFIC = {
     "workload": "gptneo125m_k8",
-    "kernel_source_sha256": "08db7cb1ed6d1ae6c5af4b9866952c3bb8da4692a4d047bfce1a95ff672c3077",
+    "kernel_source_sha256": "71eaa93e4ab6e20b25bb5295d2ac338d3362c777faafe2218fd0d8ad84f7326b",
     "bytes_per_launch": 25224103404.5,            # mean over the 16 launches t = 0..15 of the counter runs
     "algorithmic_bytes_same_launches": 25224565440.0,
 }
 
 
 def kernel_source_digest(path=None):
-    """SHA-256 of the device code of the kernel source (everything above the host-side marker) with comments
-    and white space removed: a change of kernel code changes it, a change of wording or of host code does not."""
+    """SHA-256 of the code of step_kernel and its helpers (everything above the marker that follows the
+    kernel in the source) with comments and white space removed: a change of that kernel's code changes it, a
+    change of wording, of other kernels or of host code does not."""
     import hashlib
     import re
     path = path or os.path.join(ROOT, "paper_2504_18454_amd", "csrc", "palsgd.hip")
-    text = open(path, "r").read().split("// ======== host side", 1)[0]
+    text = open(path, "r").read().split("// ======== end of the local-update kernel", 1)[0]
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     text = re.sub(r"//[^\n]*", "", text)
     text = re.sub(r"\s+", "", text)
@@ -203,6 +204,8 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
         norms = torch.empty(K, dtype=f, device=dev)
         ms = timed(lambda: ctx.palsgd_clip_grad_norm(1.0, norms, stream))
         res["clip_grad_norm"] = dict(ms=ms, gbps=float(P) * K * gB / ms / 1e6, bytes_per_elem=K * gB)
+        ms = timed(lambda: ctx.palsgd_clip_mean_grad_norm(1.0, None, norms, stream))
+        res["clip_mean_grad_norm"] = dict(ms=ms, gbps=float(P) * K * gB / ms / 1e6, bytes_per_elem=K * gB)
         ms = timed(lambda: ctx.palsgd_diagnostics(out2, stream))
         res["diagnostics"] = dict(ms=ms, gbps=float(P) * (4 * K + 4) / ms / 1e6, bytes_per_elem=4 * K + 4)
         ones, zeros = np.ones(K, np.uint8), np.zeros(K, np.uint8)
@@ -304,7 +307,7 @@ def main():
         out["hip_graph_replay"] = r["graph"]
     if a.extra_kernels:
         out["extra_kernels"] = {k: r[k] for k in ("gradient_branch_only", "mixing_branch_only", "ddp_step",
-                                                  "clip_grad_norm", "diagnostics") if k in r}
+                                                  "clip_grad_norm", "clip_mean_grad_norm", "diagnostics") if k in r}
     print(json.dumps(out))
 
 

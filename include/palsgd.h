@@ -147,8 +147,8 @@ palsgd_status palsgd_outer_step_diag(palsgd_ctx *ctx, uint64_t t, float *diag_ou
  * palsgd_capturable_begin that follows, or by palsgd_ddp_finish.
  * Precondition: all workers are identical (true from palsgd_init through the warm-up);
  * the common model is read from XG, the common InnerOPT state from worker 0.  ESTATE if
- * the workers' step counts differ.  OM is not touched.  Clipping scales left by
- * palsgd_clip_grad_norm are not consumed here. */
+ * the workers' step counts differ.  OM is not touched.  The per-worker clipping scales of
+ * palsgd_clip_grad_norm are not consumed here; the scale of palsgd_clip_mean_grad_norm is. */
 palsgd_status palsgd_ddp_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, const float *grad_scale, void *stream);
 
 /* End of the warm-up made explicit: copies worker 0's InnerOPT state into rows 1..K-1 of
@@ -166,6 +166,15 @@ palsgd_status palsgd_ddp_finish(palsgd_ctx *ctx, void *stream);
  * be issued on one stream.
  * EINVAL unless max_norm is finite and > 0. */
 palsgd_status palsgd_clip_grad_norm(palsgd_ctx *ctx, float max_norm, float *norms_out_dev, void *stream);
+
+/* Clipping in the DDP phase, where the optimizer sees the averaged gradient (Sec. 3.1):
+ * norm = |(1/K) sum_k grad_scale[k] G[k]|_2 and scale = min(1, max_norm / (norm + 1e-6))
+ * stay on the device; the next palsgd_ddp_step multiplies the averaged gradient by scale
+ * and forgets it.  Pass the same grad_scale (host, K floats, or NULL) to both calls.
+ * norm_out_dev: device float that receives the norm, or NULL.  Shares the reduction
+ * scratch and the one-stream rule of palsgd_clip_grad_norm. */
+palsgd_status palsgd_clip_mean_grad_norm(palsgd_ctx *ctx, float max_norm, const float *grad_scale,
+                                         float *norm_out_dev, void *stream);
 
 /* Diagnostics of the paper's analysis (App. A.3): out_dev[0] = consensus distance
  * Xi = (1/K) sum_k |x_k - XG|^2 (zero right after an outer step), out_dev[1] = |Delta|^2

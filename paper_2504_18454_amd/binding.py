@@ -26,7 +26,7 @@ EXPORTS = ("palsgd_layout", "palsgd_init", "palsgd_draw", "palsgd_inner_step", "
            "palsgd_step", "palsgd_outer_step", "palsgd_get_state", "palsgd_set_state",
            "palsgd_last_error", "palsgd_destroy", "palsgd_set_tuning", "palsgd_ddp_step",
            "palsgd_clip_grad_norm", "palsgd_diagnostics", "palsgd_outer_step_diag", "palsgd_capturable_begin",
-           "palsgd_step_capturable", "palsgd_capturable_end", "palsgd_ddp_finish")
+           "palsgd_step_capturable", "palsgd_capturable_end", "palsgd_ddp_finish", "palsgd_clip_mean_grad_norm")
 
 
 class PalsgdError(RuntimeError):
@@ -83,6 +83,8 @@ def lib() -> C.CDLL:
         L.palsgd_ddp_finish.argtypes = [vp, vp]
         L.palsgd_clip_grad_norm.restype = st
         L.palsgd_clip_grad_norm.argtypes = [vp, f, vp, vp]
+        L.palsgd_clip_mean_grad_norm.restype = st
+        L.palsgd_clip_mean_grad_norm.argtypes = [vp, f, C.POINTER(f), vp, vp]
         L.palsgd_diagnostics.restype = st
         L.palsgd_diagnostics.argtypes = [vp, vp, vp]
         L.palsgd_capturable_begin.restype = st
@@ -221,6 +223,12 @@ class Palsgd:
         """norms_out: torch CUDA float32 tensor of K elements (or a device address), or None."""
         ptr = None if norms_out is None else (norms_out if isinstance(norms_out, int) else norms_out.data_ptr())
         _check(lib().palsgd_clip_grad_norm(self._ctx, max_norm, ptr, _stream_handle(stream)), self._ctx)
+
+    def palsgd_clip_mean_grad_norm(self, max_norm, grad_scale=None, norm_out=None, stream=None):
+        """norm_out: torch CUDA float32 tensor of 1 element (or a device address), or None."""
+        gs, gsp = _f32(grad_scale)
+        ptr = None if norm_out is None else (norm_out if isinstance(norm_out, int) else norm_out.data_ptr())
+        _check(lib().palsgd_clip_mean_grad_norm(self._ctx, max_norm, gsp, ptr, _stream_handle(stream)), self._ctx)
 
     def palsgd_diagnostics(self, out, stream=None):
         """out: torch CUDA float32 tensor of 2 elements (or a device address): Xi, |Delta|^2."""

@@ -198,6 +198,8 @@ __global__ __launch_bounds__(kWave) void step_kernel(const StepArgs args, const 
     }
 }
 
+// ======== end of the local-update kernel and its helpers ========
+
 struct OuterArgs {
     float inv_k, lr, mu;
     int nesterov;
@@ -409,8 +411,9 @@ template <int INNER, int GDT, bool TAB>
 __global__ __launch_bounds__(kWave) void ddp_kernel(const DdpArgs a, const float* __restrict__ wd_tab,
                                                     float* __restrict__ X, float* __restrict__ M,
                                                     float* __restrict__ V, const void* __restrict__ G,
-                                                    float* __restrict__ XG, uint64_t n, uint64_t row_stride,
-                                                    uint32_t K, Hyper h) {
+                                                    float* __restrict__ XG,
+                                                    const float* __restrict__ clip_scale, uint64_t n,
+                                                    uint64_t row_stride, uint32_t K, Hyper h) {
     const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
     if (e >= n) return;
     typedef GradLoad<GDT> GL;
@@ -426,7 +429,8 @@ __global__ __launch_bounds__(kWave) void ddp_kernel(const DdpArgs a, const float
         for (int u = 0; u < 8; ++u)
             if (k0 + u < K) sum += GL::widen(t[u]) * a.w[k0 + u];
     }
-    const f4 g = sum * a.inv_k;
+    // averaged gradient, times the clipping scale of its norm if one was left on the device
+    const f4 g = sum * (clip_scale ? a.inv_k * clip_scale[0] : a.inv_k);
     const float wd = TAB ? wd_tab[e >> 6] : h.wd;
     if (INNER == PALSGD_INNER_ADAMW)
         adamw4(xv, mv, vv, g, h, a.c1, a.c2, a.lr * wd);
@@ -484,6 +488,38 @@ __global__ __launch_bounds__(kWave) void sumsq_kernel(const void* __restrict__ G
     }
     acc = wave_sum(acc);
     if (threadIdx.x == 0) partial[(uint64_t)blockIdx.y * per_row + blockIdx.x] = acc;
+}
+
+// Sum of squares of the averaged gradient (1/K) sum_k w_k g_k, per wavefront of two tiles
+// (clipping in the DDP phase, where the optimizer sees the averaged gradient, Sec. 3.1).
+constexpr int kMeanTiles = 2;
+template <int GDT>
+__global__ __launch_bounds__(kWave) void sumsq_mean_kernel(const void* __restrict__ G, const DdpArgs a,
+                                                           float* __restrict__ partial, uint64_t n,
+                                                           uint64_t row_stride, uint32_t K) {
+    typedef GradLoad<GDT> GL;
+    const uint64_t base = (uint64_t)blockIdx.x * (kTile * kMeanTiles) + threadIdx.x * 4;
+    float acc = 0.f;
+#pragma unroll
+    for (int u = 0; u < kMeanTiles; ++u) {
+        const uint64_t e = base + (uint64_t)u * kTile;
+        if (e < n) {
+            f4 sum = {0.f, 0.f, 0.f, 0.f};
+            for (uint32_t k0 = 0; k0 < K; k0 += 8) {
+                typename GL::raw t[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (k0 + q < K) t[q] = GL::load(G, (uint64_t)(k0 + q) * row_stride + e);
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    if (k0 + q < K) sum += GL::widen(t[q]) * a.w[k0 + q];
+            }
+            const f4 g = sum * a.inv_k;
+            acc += (g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w);
+        }
+    }
+    acc = wave_sum(acc);
+    if (threadIdx.x == 0) partial[blockIdx.x] = acc;
 }
 
 // Fixed-order sum of `count` values in double by one workgroup; every thread returns the total.
@@ -612,6 +648,7 @@ struct palsgd_ctx {
     float* d_wd_tab = nullptr;     // else: weight_decay * multiplier per 64 elements of a row
     float* d_scratch = nullptr;    // partial sums of the scalar reductions + their K+2 results
     bool clip_armed = false;       // d_scratch holds clipping scales for the next gradient step
+    bool clip_mean_armed = false;  // ... and the scale of the averaged gradient for the next DDP step
     bool moments_shared = false;   // after DDP steps: only replica 0's M, V are current
     void* d_schedule = nullptr;    // DevSchedule of the graph-capturable mode
     bool capturable = false;       // between palsgd_capturable_begin and palsgd_capturable_end
@@ -713,8 +750,9 @@ palsgd_status check_launch(palsgd_ctx* c, const char* what) {
     return PALSGD_OK;
 }
 
-// Scratch layout (floats): [0, 64) clipping scales | 64 * kFold doubles of second-stage sums |
-// first-stage partial sums (one per wavefront of the producing kernel).
+// Scratch layout (floats): [0, 64) per-worker clipping scales | [64] clipping scale of the averaged
+// gradient | from 128: 64 * kFold doubles of second-stage sums | first-stage partial sums (one per
+// wavefront of the producing kernel).
 uint32_t norm_parts(const palsgd_ctx* c) {
     return (uint32_t)((c->P_padded + (uint64_t)kTile * kNormTiles - 1) / ((uint64_t)kTile * kNormTiles));
 }
@@ -723,14 +761,15 @@ uint32_t diag_parts(const palsgd_ctx* c) {
 }
 uint32_t tile_count(const palsgd_ctx* c) { return (uint32_t)((c->P_padded + kTile - 1) / kTile); }
 float* clip_scales(palsgd_ctx* c) { return c->d_scratch; }
-double* scratch_fold(palsgd_ctx* c) { return (double*)(c->d_scratch + PALSGD_MAX_K); }
-float* scratch_partials(palsgd_ctx* c) { return c->d_scratch + PALSGD_MAX_K + 2 * PALSGD_MAX_K * kFold; }
+float* mean_clip_scale(palsgd_ctx* c) { return c->d_scratch + PALSGD_MAX_K; }
+double* scratch_fold(palsgd_ctx* c) { return (double*)(c->d_scratch + 2 * PALSGD_MAX_K); }
+float* scratch_partials(palsgd_ctx* c) { return c->d_scratch + 2 * PALSGD_MAX_K + 2 * PALSGD_MAX_K * kFold; }
 
 palsgd_status ensure_scratch(palsgd_ctx* c) {
     if (c->d_scratch) return PALSGD_OK;
     uint64_t parts = (uint64_t)c->cfg.K * norm_parts(c);
     if (parts < 2ull * tile_count(c)) parts = 2ull * tile_count(c);  // fused diagnostics: two per tile
-    uint64_t floats = PALSGD_MAX_K + 2ull * PALSGD_MAX_K * kFold + parts;
+    uint64_t floats = 2ull * PALSGD_MAX_K + 2ull * PALSGD_MAX_K * kFold + parts;
     float* d = nullptr;
     hipError_t e = hipMalloc(&d, floats * sizeof(float));
     if (e != hipSuccess) {
@@ -1086,11 +1125,12 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
     Hyper h{ctx->cfg.beta1, ctx->cfg.beta2, ctx->cfg.eps, ctx->cfg.momentum, ctx->wd_eff0};
     hipStream_t st = (hipStream_t)stream;
     const palsgd_buffers& b = ctx->buf;
+    const float* clip = ctx->clip_mean_armed ? mean_clip_scale(ctx) : nullptr;
 #define PALSGD_DDP(I, D)                                                                                           \
     if (ctx->wd_uniform)                                                                                           \
-        ddp_kernel<I, D, false><<<tiles, kWave, lds, st>>>(a, nullptr, b.X, b.M, b.V, b.G, b.XG, n, b.row_stride, K, h); \
+        ddp_kernel<I, D, false><<<tiles, kWave, lds, st>>>(a, nullptr, b.X, b.M, b.V, b.G, b.XG, clip, n, b.row_stride, K, h); \
     else                                                                                                           \
-        ddp_kernel<I, D, true><<<tiles, kWave, lds, st>>>(a, ctx->d_wd_tab, b.X, b.M, b.V, b.G, b.XG, n, b.row_stride, K, h);
+        ddp_kernel<I, D, true><<<tiles, kWave, lds, st>>>(a, ctx->d_wd_tab, b.X, b.M, b.V, b.G, b.XG, clip, n, b.row_stride, K, h);
     if (adamw && bf16) { PALSGD_DDP(PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16) }
     else if (adamw) { PALSGD_DDP(PALSGD_INNER_ADAMW, PALSGD_GRAD_F32) }
     else if (bf16) { PALSGD_DDP(PALSGD_INNER_SGDM, PALSGD_GRAD_BF16) }
@@ -1100,6 +1140,7 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
     if (rc != PALSGD_OK) return rc;
     for (uint32_t k = 0; k < K; ++k) ctx->tau[k] += 1;
     ctx->moments_shared = true;
+    ctx->clip_mean_armed = false;
     return PALSGD_OK;
 }
 
@@ -1136,6 +1177,50 @@ palsgd_status palsgd_clip_grad_norm(palsgd_ctx* ctx, float max_norm, float* norm
     rc = check_launch(ctx, "palsgd_clip_grad_norm");
     if (rc != PALSGD_OK) return rc;
     ctx->clip_armed = true;
+    return PALSGD_OK;
+}
+
+palsgd_status palsgd_clip_mean_grad_norm(palsgd_ctx* ctx, float max_norm, const float* grad_scale,
+                                         float* norm_out_dev, void* stream) {
+    if (!ctx) {
+        set_error(g_error, "palsgd_clip_mean_grad_norm: NULL context");
+        return PALSGD_EINVAL;
+    }
+    if (!(max_norm > 0.0f) || !std::isfinite(max_norm)) {
+        set_error(ctx->error, "palsgd_clip_mean_grad_norm: max_norm must be finite and > 0");
+        return PALSGD_EINVAL;
+    }
+    const uint32_t K = ctx->cfg.K;
+    DdpArgs a;
+    for (uint32_t k = 0; k < PALSGD_MAX_K; ++k) a.w[k] = 1.0f;
+    if (grad_scale)
+        for (uint32_t k = 0; k < K; ++k) {
+            if (!std::isfinite(grad_scale[k])) {
+                set_error(ctx->error, "palsgd_clip_mean_grad_norm: grad_scale[%u] is not finite", k);
+                return PALSGD_EINVAL;
+            }
+            a.w[k] = grad_scale[k];
+        }
+    a.inv_k = (float)(1.0 / (double)K);
+    a.lr = a.c1 = a.c2 = 0.0f;
+    palsgd_status rc = ensure_scratch(ctx);
+    if (rc != PALSGD_OK) return rc;
+    const uint64_t span = (uint64_t)kTile * kMeanTiles;
+    const uint32_t parts = (uint32_t)((ctx->P_padded + span - 1) / span);
+    const uint32_t gbytes = ctx->cfg.grad_dtype == PALSGD_GRAD_BF16 ? 2u : 4u;
+    const uint32_t lds = lds_cap(auto_waves(gbytes * K * kTile * kMeanTiles, 4), 0);
+    hipStream_t st = (hipStream_t)stream;
+    if (ctx->cfg.grad_dtype == PALSGD_GRAD_BF16)
+        sumsq_mean_kernel<PALSGD_GRAD_BF16><<<parts, kWave, lds, st>>>(ctx->buf.G, a, scratch_partials(ctx),
+                                                                      ctx->P_padded, ctx->buf.row_stride, K);
+    else
+        sumsq_mean_kernel<PALSGD_GRAD_F32><<<parts, kWave, lds, st>>>(ctx->buf.G, a, scratch_partials(ctx),
+                                                                     ctx->P_padded, ctx->buf.row_stride, K);
+    fold_kernel<<<dim3(kFold, 1), kThreads, 0, st>>>(scratch_partials(ctx), parts, scratch_fold(ctx));
+    clip_finish_kernel<<<1, kThreads, 0, st>>>(scratch_fold(ctx), max_norm, mean_clip_scale(ctx), norm_out_dev);
+    rc = check_launch(ctx, "palsgd_clip_mean_grad_norm");
+    if (rc != PALSGD_OK) return rc;
+    ctx->clip_mean_armed = true;
     return PALSGD_OK;
 }
 

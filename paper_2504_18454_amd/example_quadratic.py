@@ -41,6 +41,7 @@ def run(K=8, numels=(50000, 1000, 64), warmup=20, steps=200, H=10, p=0.1, alpha=
 
     for t in range(warmup):                       # DDP warm-up: every worker applies the averaged gradient
         gradients()
+        opt.palsgd_clip_mean_grad_norm(clip)      # DDP clips the averaged gradient
         opt.palsgd_ddp_step(t, alpha)
     for t in range(steps):                        # PALSGD phase, t counted from 0 again
         gradients()

@@ -179,12 +179,23 @@ class Run:
                 self.compare()
         torch.cuda.synchronize()
 
-    def ddp_iterate(self, steps, grad_scale=None):
-        """DDP warm-up steps: every worker applies the update of the averaged gradient."""
+    def ddp_iterate(self, steps, grad_scale=None, clip=None):
+        """DDP warm-up steps: every worker applies the update of the averaged gradient (clipped by the
+        norm of that average when `clip` is given; a whole-row reduction, so full-coverage runs only)."""
         gs64 = None if grad_scale is None else np.asarray(grad_scale, np.float32).astype(np.float64)
         for _ in range(steps):
             self.make_gradients()
-            self.ora.ddp_step(self.alpha, grad_scale=gs64)
+            gs_o = gs64
+            if clip is not None:
+                assert self.full
+                norm_dev = torch.empty(1, dtype=torch.float32, device=self.dev)
+                self.lib.palsgd_clip_mean_grad_norm(clip, grad_scale, norm_dev)
+                norm = self.ora.mean_grad_norm(gs64)
+                np.testing.assert_allclose(float(norm_dev), norm, rtol=1e-5)
+                scale = oracle.clip_scale(norm, float(np.float32(clip)))
+                gs_o = (np.ones(self.K) if gs64 is None else gs64) * scale
+                self.last_scales = np.array([scale])
+            self.ora.ddp_step(self.alpha, grad_scale=gs_o)
             self.lib.palsgd_ddp_step(self.t, self.alpha, grad_scale)
             self.t += 1
         torch.cuda.synchronize()

@@ -147,6 +147,12 @@ def test_reductions_full_size_on_seeded_inputs(name):
         assert float(norms[k]) == pytest.approx(oracle.grad_norm(np.ascontiguousarray(g)), rel=1e-5)
     xi, d2 = oracle.diagnostics(X.cpu().numpy(), XG.cpu().numpy())
     assert out.cpu().tolist() == pytest.approx([xi, d2], rel=1e-5)
+    mean_norm = torch.empty(1, dtype=f, device=dev)
+    lib.palsgd_clip_mean_grad_norm(1.0, None, mean_norm)
+    torch.cuda.synchronize()
+    Gh = G.cpu()
+    Gh = Gh.numpy() if w.grad_dtype == "f32" else Gh.view(torch.int16).numpy().view(np.uint16)
+    assert float(mean_norm) == pytest.approx(oracle.mean_grad_norm(np.ascontiguousarray(Gh)), rel=1e-5)
     out2 = torch.empty(2, dtype=f, device=dev)
     lib.palsgd_outer_step_diag(0, out2)                 # same inputs: the fused reduction must give the same scalars
     assert out2.cpu().tolist() == pytest.approx([xi, d2], rel=1e-5)
@@ -175,3 +181,18 @@ def test_worked_example_converges():
     assert errs[-1] < 0.05 and errs[-1] < errs[0]
     assert all(h[2] > 0 and h[3] > 0 for h in history)
     assert after == [0.0, 0.0]
+
+
+@pytest.mark.parametrize("inner,grad_dtype,K,max_norm", [("adamw", "f32", 4, 2.0), ("adamw", "bf16", 8, 3.0),
+                                                         ("sgdm", "f32", 1, 5.0), ("adamw", "bf16", 33, 1e6)])
+def test_ddp_with_clipping_of_the_averaged_gradient(inner, grad_dtype, K, max_norm):
+    r = _run(K=K, numels=RAGGED, inner=inner, grad_dtype=grad_dtype, p=0.2, H=4, seed=37 + K, sigma=0.5)
+    gs = [1.0, 0.5, 2.0, 1.0] if K == 4 else None
+    r.ddp_iterate(6, grad_scale=gs, clip=max_norm)
+    r.lib.palsgd_ddp_finish()
+    r.compare()
+    assert (r.last_scales < 1.0).all() if max_norm < 1e5 else (r.last_scales == 1.0).all()
+    r.ddp_iterate(2, grad_scale=gs)                     # the scale is consumed once: these steps are unclipped
+    r.iterate(5)
+    r.compare()
+    r.close()
