@@ -1208,7 +1208,8 @@ palsgd_status palsgd_clip_mean_grad_norm(palsgd_ctx* ctx, float max_norm, const 
     const uint64_t span = (uint64_t)kTile * kMeanTiles;
     const uint32_t parts = (uint32_t)((ctx->P_padded + span - 1) / span);
     const uint32_t gbytes = ctx->cfg.grad_dtype == PALSGD_GRAD_BF16 ? 2u : 4u;
-    const uint32_t lds = lds_cap(auto_waves(gbytes * K * kTile * kMeanTiles, 4), 0);
+    // a wavefront has at most eight row loads in flight at a time: size the cap on those
+    const uint32_t lds = lds_cap(auto_waves(gbytes * (K < 8 ? K : 8u) * kTile, 4), 0);
     hipStream_t st = (hipStream_t)stream;
     if (ctx->cfg.grad_dtype == PALSGD_GRAD_BF16)
         sumsq_mean_kernel<PALSGD_GRAD_BF16><<<parts, kWave, lds, st>>>(ctx->buf.G, a, scratch_partials(ctx),
