@@ -121,7 +121,8 @@ __device__ __forceinline__ void adamw4(f4& x, f4& m, f4& v, f4 g, const Hyper& h
         float mi = fmaf(h.beta1, m[i], (1.0f - h.beta1) * g[i]);
         float vi = fmaf(h.beta2, v[i], (1.0f - h.beta2) * g[i] * g[i]);
         float denom = fmaf(sqrtf(vi), c2, h.eps);
-        x[i] = fmaf(-c1, mi / denom, fmaf(-decay, x[i], x[i]));
+        // the whole step first (small, so its rounding is far below an ulp of x), then ONE rounding of x
+        x[i] = x[i] - fmaf(c1, mi / denom, decay * x[i]);
         m[i] = mi;
         v[i] = vi;
     }

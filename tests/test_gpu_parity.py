@@ -276,23 +276,14 @@ def test_non_finite_gradients_stay_where_they_are():
     r.close()
 
 
-def test_long_run_in_windows_of_64_steps():
-    """1536 steps (96 synchronisations, step counts up to about 1400) in 24 windows of 64 steps.  The parity
-    harness is open-loop on the device side: gradients follow the oracle's x_k, so a rounding difference on
-    the device sees no restoring force and random-walks, amplified by the outer momentum's 1/(1-mu) gain
-    (measured without windows: max |x - oracle| grows from 2e-7 after 250 steps to 1.4e-5 after 1500, and with
-    |x| of order 1 a 256-step window already reaches the tolerance on the worst 0.07 % of elements).  Each window
-    therefore starts from the oracle's state, written into the device buffers.  X, M, V, XG must end each
-    window within the per-element tolerance.  The outer momentum is a geometric sum of model differences, so
-    once |x| has grown to order 1 and |OM| has shrunk (the run converges) its error is set by the models'
-    rounding, not by its own size: it is held to the bound that models within tolerance imply,
-    2 tol_x / (1 - mu) on top of its own tolerance."""
+def test_long_run_stays_within_tolerance():
+    """1500 steps (93 synchronisations, step counts up to about 1400), six times the longest configuration.  The
+    harness is open-loop on the device side (gradients follow the oracle's x_k), so device-side rounding
+    differences see no restoring force and random-walk; with one rounding per stored value in every kernel
+    they stay far inside the per-element tolerance over this horizon (about 0.25 of the bound at worst)."""
     r = _run(K=4, numels=[20000, 64, 333, 5000], inner="adamw", grad_dtype="bf16", p=0.1, H=16, seed=25, sigma=0.05)
-    worst = {}
-    for w in range(24):
-        r.iterate(64)
-        for k, v in r.compare(om_propagated=True).items():
-            worst[k] = max(worst.get(k, 0.0), v)
-        r.reseed_device_from_oracle()
-    print("worst err/bound over the windows", worst)
+    r.iterate(1500, check_every=250)
+    worst = r.compare()
+    print("worst err/bound", worst)
+    assert max(worst.values()) < 0.5
     r.close()
