@@ -71,7 +71,7 @@ def grad_bytes_per_elem(inner: str, grad_dtype: str) -> int:
     return (24 if inner == "adamw" else 16) + g          # read+write x,m(,v) + read g
 
 
-def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=False, graph=False):
+def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=False, graph=False, wd_mult=None):
     import torch
 
     from paper_2504_18454_amd import Palsgd, make_config, palsgd_layout
@@ -81,7 +81,7 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     dev = torch.device("cuda:0")
     cfg = make_config(w.K, w.numels, inner=w.inner, grad_dtype=w.grad_dtype, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
                       weight_decay=w.weight_decay, momentum=w.momentum, p=w.p, H=w.H, outer_lr=w.outer_lr,
-                      outer_momentum=w.outer_momentum, outer_nesterov=w.outer_nesterov, seed=w.seed)
+                      outer_momentum=w.outer_momentum, outer_nesterov=w.outer_nesterov, seed=w.seed, wd_mult=wd_mult)
     row, offs = palsgd_layout(cfg)
     K = w.K
     gen = torch.Generator(device=dev)
@@ -266,6 +266,8 @@ def main():
     ap.add_argument("--outer-waves", type=int, default=0, help="resident wavefronts per CU, outer step (0 = library's choice)")
     ap.add_argument("--outer-variant", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decay-1d", action="store_true",
+                    help="weight-decay multiplier 0 on one-dimensional tensors (biases, norms): exercises the per-tensor table")
     ap.add_argument("--graph", action="store_true",
                     help="also time windows of H steps + outer step replayed from one HIP graph (device-resident schedule)")
     ap.add_argument("--extra-kernels", action="store_true",
@@ -277,7 +279,8 @@ def main():
         sys.exit(2)
     from paper_2504_18454_amd.workloads import workload
     w = workload(a.workload)
-    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph)
+    wd_mult = [0.0 if len(shape) == 1 else 1.0 for _, shape in w.tensors] if a.no_decay_1d else None
+    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph, wd_mult)
     cpu = None
     if not a.no_cpu_baseline:
         cpu = run_cpu_baseline(w)
@@ -292,7 +295,8 @@ def main():
         "config": {"workload": a.workload, "K": w.K, "P": w.P, "tensors": len(w.tensors), "inner": w.inner,
                    "grad_dtype": w.grad_dtype, "p": w.p, "H": w.H, "eta": w.eta, "alpha": w.alpha,
                    "outer": f"nesterov lr {w.outer_lr} mu {w.outer_momentum}", "outer_steps_timed": r["n_outer"],
-                   "mix_fraction_timed": round(r["mix_fraction"], 4)},
+                   "mix_fraction_timed": round(r["mix_fraction"], 4),
+                   "weight_decay": "uniform" if not a.no_decay_1d else "per tensor: 0 on 1-D tensors"},
         "hbm_GBps_whole_step": r["blended_gbps"], "hbm_frac_whole_step": r["blended_gbps"] / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": r["step_kernel_gbps"],
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": r["step_kernel_gbps"] / HBM_PEAK_GBPS,
