@@ -287,3 +287,15 @@ def test_long_run_stays_within_tolerance():
     print("worst err/bound", worst)
     assert max(worst.values()) < 0.5
     r.close()
+
+
+def test_c_abi_from_plain_c():
+    """The same path driven from a C program: HIP runtime allocations, include/palsgd.h, the oracle's C routines
+    as the reference; no Python, no PyTorch in that process."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi_parity")
+    assert os.path.exists(exe), "tests/c_abi_parity is built by __graft_entry__.build()"
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    print(out.stdout.strip())
+    assert out.returncode == 0 and "PASS" in out.stdout, (out.returncode, out.stdout, out.stderr)

@@ -153,3 +153,15 @@ def test_binding_structs_match_the_header_layout(tmp_path):
     assert out[len(want)].split() == ["0", "1", "2", "3", "4"]
     assert (binding.PALSGD_OK, binding.PALSGD_EINVAL, binding.PALSGD_ENOMEM, binding.PALSGD_EHIP, binding.PALSGD_ESTATE) == (0, 1, 2, 3, 4)
     assert int(out[len(want) + 1]) == binding.MAX_K
+
+
+def test_plain_c_program_is_built_and_fails_cleanly_without_a_gpu():
+    """tests/c_abi_parity links against the library and the HIP runtime; without a device it stops at its
+    first allocation with an error message (on a GPU machine it runs to completion, see the GPU tests)."""
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi_parity")
+    if not os.path.exists(exe):
+        pytest.skip("tests/c_abi_parity has not been built (python -c 'import __graft_entry__ as g; g.build()')")
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert out.returncode in (0, 2), (out.returncode, out.stderr)
+    assert ("HIP error" in out.stderr) if out.returncode == 2 else ("PASS" in out.stdout)
