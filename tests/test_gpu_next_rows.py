@@ -69,9 +69,9 @@ def test_ddp_rejects_diverged_workers():
     r.close()
 
 
-@pytest.mark.parametrize("grad_dtype,max_norm", [("f32", 5.0), ("bf16", 50.0), ("f32", 1e6)])
+@pytest.mark.parametrize("grad_dtype,max_norm", [("f32", 5.0), ("bf16", 20.0), ("f32", 1e6)])
 def test_clip_grad_norm_in_the_loop(grad_dtype, max_norm):
-    r = _run(K=4, numels=RAGGED, grad_dtype=grad_dtype, p=0.3, H=4, seed=32, sigma=0.5)
+    r = _run(K=4, numels=RAGGED, grad_dtype=grad_dtype, p=0.3, H=4, seed=32, sigma=0.1, c_scale=0.25)
     r.iterate(9, clip=max_norm, grad_scale=[1.0, 0.5, 1.0, 2.0])
     r.compare()
     if max_norm < 1e5:
@@ -186,7 +186,7 @@ def test_worked_example_converges():
 @pytest.mark.parametrize("inner,grad_dtype,K,max_norm", [("adamw", "f32", 4, 2.0), ("adamw", "bf16", 8, 3.0),
                                                          ("sgdm", "f32", 1, 5.0), ("adamw", "bf16", 33, 1e6)])
 def test_ddp_with_clipping_of_the_averaged_gradient(inner, grad_dtype, K, max_norm):
-    r = _run(K=K, numels=RAGGED, inner=inner, grad_dtype=grad_dtype, p=0.2, H=4, seed=37 + K, sigma=0.5)
+    r = _run(K=K, numels=RAGGED, inner=inner, grad_dtype=grad_dtype, p=0.2, H=4, seed=37 + K, sigma=0.1, c_scale=0.25)
     gs = [1.0, 0.5, 2.0, 1.0] if K == 4 else None
     r.ddp_iterate(6, grad_scale=gs, clip=max_norm)
     r.lib.palsgd_ddp_finish()

@@ -28,15 +28,16 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib(), n), n
 
 
-def test_layout_pads_to_64_and_matches_generator_layout():
+def test_layout_pads_tensors_to_64_rows_to_256_and_matches_generator_layout():
     for name in WORKLOADS:
         w = workload(name)
         P, offs = palsgd_layout(make_config(w.K, w.numels))
         goffs, grow = flat_layout(w.numels)
         assert (P, offs) == (grow, goffs)
-        assert all(o % 64 == 0 for o in offs) and P % 64 == 0 and P >= w.P
-    assert palsgd_layout(make_config(1, [1])) == (64, [0])
+        assert all(o % 64 == 0 for o in offs) and P % 256 == 0 and P >= w.P
+    assert palsgd_layout(make_config(1, [1])) == (256, [0])
     assert palsgd_layout(make_config(1, [64, 65, 1])) == (256, [0, 64, 192])
+    assert palsgd_layout(make_config(1, [250, 7])) == (512, [0, 256])
 
 
 def _init(cfg, **over):
@@ -54,8 +55,8 @@ def test_init_rejects_bad_arguments_without_touching_the_device():
         dict(cfg=dict(inner="sgdm", momentum=1.0)), dict(cfg=dict(outer_momentum=1.5)),
         dict(cfg=dict(outer_lr=float("inf"))), dict(cfg=dict(weight_decay=-1.0)),
         dict(cfg=dict(wd_mult=[1.0, float("nan")])),
-        dict(buf=dict(X=None)), dict(buf=dict(V=None)), dict(buf=dict(G=FAKE + 4)), dict(buf=dict(row_stride=64)),
-        dict(buf=dict(row_stride=128 + 32)),
+        dict(buf=dict(X=None)), dict(buf=dict(V=None)), dict(buf=dict(G=FAKE + 4)), dict(buf=dict(row_stride=192)),
+        dict(buf=dict(row_stride=256 + 32)),
     ]
     for case in bad:
         kw = dict(K=4)

@@ -140,8 +140,16 @@ def test_brute_force_tiny(oracle_mod, K, H, numels, inner, nesterov):
     assert 0 < mixed < 12 * K or K * 12 < 20      # both branches were exercised
 
 
-def _quadratic_grads(X, c, noise):
-    return ((X.astype(np.float64) - c[None]) + noise).astype(f32)
+def _quadratic_grads(X, c, noise, numels=None):
+    """g_k = (x_k - c) + noise on tensor elements, zero on the padding of the flat row."""
+    g = ((X.astype(np.float64) - c[None]) + noise).astype(f32)
+    if numels is not None:
+        offs, row = flat_layout(numels)
+        pad = np.ones(row, bool)
+        for o, n in zip(offs, numels):
+            pad[o:o + n] = False
+        g[:, pad] = 0
+    return g
 
 
 def test_p_zero_is_diloco_library_loop(oracle_mod):
@@ -159,7 +167,7 @@ def test_p_zero_is_diloco_library_loop(oracle_mod):
              for w in workers]
     for t in range(T):
         noise = 0.01 * rng.standard_normal((K, row))
-        G = _quadratic_grads(st.X, c, noise)
+        G = _quadratic_grads(st.X, c, noise, numels)
         st.G[...] = G
         mask, synced = st.iteration(t, 1e-3, 16.0)
         assert not mask.any()
@@ -187,8 +195,8 @@ def test_p_zero_outer_sgd_is_local_sgd(oracle_mod):
                 outer_lr=1.0, outer_momentum=0.0, outer_nesterov=False)
     W = np.tile(x0.astype(np.float64), (K, 1))
     for t in range(T):
-        noise = 0.05 * rng.standard_normal((K, 64))
-        G = _quadratic_grads(st.X, c, noise)
+        noise = 0.05 * rng.standard_normal(st.X.shape)
+        G = _quadratic_grads(st.X, c, noise, numels)
         st.G[...] = G
         st.iteration(t, lr, 1.0)
         W = W - lr * G
@@ -322,7 +330,7 @@ def test_theorem_parameters_contract_on_quadratic(oracle_mod):
         eta = F(p / (2 * H * alpha))
         d0 = np.linalg.norm(x0 - c)
         for t in range(T):
-            st.G[...] = _quadratic_grads(st.X, c, 0.5 * rng.standard_normal(st.X.shape))
+            st.G[...] = _quadratic_grads(st.X, c, 0.5 * rng.standard_normal(st.X.shape), numels)
             st.iteration(t, alpha, eta)
         return np.linalg.norm(st.XG - c) / d0
     e2, e16 = run(2, 5), run(16, 5)
