@@ -71,7 +71,8 @@ def grad_bytes_per_elem(inner: str, grad_dtype: str) -> int:
     return (24 if inner == "adamw" else 16) + g          # read+write x,m(,v) + read g
 
 
-def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=False, graph=False, wd_mult=None):
+def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=False, graph=False, wd_mult=None,
+            fused_sync=False):
     import torch
 
     from paper_2504_18454_amd import Palsgd, make_config, palsgd_layout
@@ -124,6 +125,12 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     def one(t, ev=None):
         if ev is not None:
             ev[0].record(stream)
+        if fused_sync and (t + 1) % w.H == 0:          # the synchronisation step as one launch
+            ctx.palsgd_step_sync(t, w.alpha, w.eta, None, None, stream)
+            if ev is not None:
+                ev[1].record(stream)
+                ev[2].record(stream)
+            return True
         ctx.palsgd_step(t, w.alpha, w.eta, None, None, stream)
         if ev is not None:
             ev[1].record(stream)
@@ -149,11 +156,14 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
 
     P = w.P
     gb, mb = grad_bytes_per_elem(w.inner, w.grad_dtype), 12
-    step_ms = [events[i][0].elapsed_time(events[i][1]) for i in range(steps)]
-    step_bytes = [float(P) * ((K - int(m.sum())) * gb + int(m.sum()) * mb) for m in masks]
+    all_ms = [events[i][0].elapsed_time(events[i][1]) for i in range(steps)]
+    all_bytes = [float(P) * ((K - int(m.sum())) * gb + int(m.sum()) * mb) for m in masks]
+    plain = [i for i in range(steps) if not (fused_sync and synced[i])]      # launches of step_kernel
+    step_ms, step_bytes = [all_ms[i] for i in plain], [all_bytes[i] for i in plain]
     outer_ms = [events[i][1].elapsed_time(events[i][2]) for i in range(steps) if synced[i]]
     outer_bytes = float(P) * (8 * K + 16)
-    total_bytes = sum(step_bytes) + outer_bytes * len(outer_ms)
+    total_bytes = sum(all_bytes) + outer_bytes * len(outer_ms)
+    fused_ms = [all_ms[i] for i in range(steps) if fused_sync and synced[i]]
     res = dict(
         elapsed=elapsed, updates=float(K) * P * steps, row=row,
         step_kernel_ms=float(np.mean(step_ms)), step_kernel_gbps=sum(step_bytes) / (sum(step_ms) * 1e-3) / 1e9,
@@ -161,6 +171,7 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
         outer_kernel_ms=float(np.mean(outer_ms)) if outer_ms else None,
         outer_kernel_gbps=(outer_bytes / (np.mean(outer_ms) * 1e-3) / 1e9) if outer_ms else None,
         n_outer=len(outer_ms), mix_fraction=float(np.mean([m.mean() for m in masks])),
+        fused_sync_ms=float(np.mean(fused_ms)) if fused_ms else None,
         blended_gbps=total_bytes / elapsed / 1e9,
     )
     torch.cuda.synchronize()
@@ -256,6 +267,11 @@ def run_cpu_baseline(w, slice_div=2, threads=None):
                        f"{steps} steps incl. one outer step, {dt:.1f} s")
 
 
+def K_bytes(w):
+    """Algorithmic bytes per element of a fused synchronisation step with every replica on the gradient branch."""
+    return w.K * (grad_bytes_per_elem(w.inner, w.grad_dtype) - 4) + 16 + 4 * w.K
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -268,6 +284,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decay-1d", action="store_true",
                     help="weight-decay multiplier 0 on one-dimensional tensors (biases, norms): exercises the per-tensor table")
+    ap.add_argument("--fused-sync", action="store_true",
+                    help="synchronisation steps as ONE launch (palsgd_step_sync) instead of palsgd_step + palsgd_outer_step")
     ap.add_argument("--graph", action="store_true",
                     help="also time windows of H steps + outer step replayed from one HIP graph (device-resident schedule)")
     ap.add_argument("--extra-kernels", action="store_true",
@@ -280,7 +298,7 @@ def main():
     from paper_2504_18454_amd.workloads import workload
     w = workload(a.workload)
     wd_mult = [0.0 if len(shape) == 1 else 1.0 for _, shape in w.tensors] if a.no_decay_1d else None
-    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph, wd_mult)
+    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph, wd_mult, a.fused_sync)
     cpu = None
     if not a.no_cpu_baseline:
         cpu = run_cpu_baseline(w)
@@ -307,6 +325,11 @@ def main():
                          "bytes_per_elem": 8 * w.K + 16},
         "cpu_baseline": cpu,
     }
+    if a.fused_sync:
+        out["config"]["sync_steps"] = "fused (palsgd_step_sync)"
+        out["outer_kernel"] = None
+        out["sync_step_kernel"] = {"ms_per_launch": r["fused_sync_ms"],
+                                   "bytes_per_elem_all_gradient": K_bytes(w), "unit": "ms"}
     if a.graph:
         out["hip_graph_replay"] = r["graph"]
     if a.extra_kernels:

@@ -128,6 +128,14 @@ palsgd_status palsgd_pseudo_sync(palsgd_ctx *ctx, uint64_t t, float alpha_t, flo
 palsgd_status palsgd_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, float eta_t,
                           const float *grad_scale, const uint8_t *mask_override, void *stream);
 
+/* Step t of Alg. 1 when (t+1) mod H == 0, whole: palsgd_step followed by
+ * palsgd_outer_step in ONE launch, with identical results.  The local update's new x_k
+ * stay in registers and go straight into the outer gradient, which saves one write and
+ * one read of the K rows of X (8K of 34K+16 bytes per element with AdamW).  Arguments as
+ * palsgd_step. */
+palsgd_status palsgd_step_sync(palsgd_ctx *ctx, uint64_t t, float alpha_t, float eta_t,
+                               const float *grad_scale, const uint8_t *mask_override, void *stream);
+
 /* Outer step (Alg. 1, the two lines of the synchronisation branch; Sec. 4.2):
  * Delta = XG - (1/K) sum_k X[k];  OM <- mu OM + Delta;
  * XG <- XG - outer_lr (Delta + mu OM) (Nesterov) or XG - outer_lr OM;  X[k] <- XG for
@@ -204,7 +212,7 @@ palsgd_status palsgd_diagnostics(palsgd_ctx *ctx, float *out_dev, void *stream);
  * palsgd_capturable_end: waits for `stream`, reads t and the step counts back (t_out may be
  *   NULL) and returns the context to host-driven calls.
  * While the schedule is device-resident, palsgd_inner_step, palsgd_pseudo_sync, palsgd_step,
- * palsgd_ddp_step, palsgd_get_state and palsgd_set_state return ESTATE. */
+ * palsgd_step_sync, palsgd_ddp_step, palsgd_get_state and palsgd_set_state return ESTATE. */
 palsgd_status palsgd_capturable_begin(palsgd_ctx *ctx, uint64_t t0, void *stream);
 palsgd_status palsgd_step_capturable(palsgd_ctx *ctx, const float *alpha_eta_dev, void *stream);
 palsgd_status palsgd_capturable_end(palsgd_ctx *ctx, uint64_t *t_out, void *stream);

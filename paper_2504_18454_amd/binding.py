@@ -26,7 +26,7 @@ EXPORTS = ("palsgd_layout", "palsgd_init", "palsgd_draw", "palsgd_inner_step", "
            "palsgd_step", "palsgd_outer_step", "palsgd_get_state", "palsgd_set_state",
            "palsgd_last_error", "palsgd_destroy", "palsgd_set_tuning", "palsgd_ddp_step",
            "palsgd_clip_grad_norm", "palsgd_diagnostics", "palsgd_outer_step_diag", "palsgd_capturable_begin",
-           "palsgd_step_capturable", "palsgd_capturable_end", "palsgd_ddp_finish", "palsgd_clip_mean_grad_norm")
+           "palsgd_step_capturable", "palsgd_capturable_end", "palsgd_ddp_finish", "palsgd_clip_mean_grad_norm", "palsgd_step_sync")
 
 
 class PalsgdError(RuntimeError):
@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
         L.palsgd_pseudo_sync.argtypes = [vp, u64, f, f, C.POINTER(C.c_uint8), vp]
         L.palsgd_step.restype = st
         L.palsgd_step.argtypes = [vp, u64, f, f, C.POINTER(f), C.POINTER(C.c_uint8), vp]
+        L.palsgd_step_sync.restype = st
+        L.palsgd_step_sync.argtypes = [vp, u64, f, f, C.POINTER(f), C.POINTER(C.c_uint8), vp]
         L.palsgd_outer_step.restype = st
         L.palsgd_outer_step.argtypes = [vp, u64, vp]
         L.palsgd_ddp_step.restype = st
@@ -208,6 +210,11 @@ class Palsgd:
         gs, gsp = _f32(grad_scale)
         mo, mop = _u8(mask_override)
         _check(lib().palsgd_step(self._ctx, int(t), alpha_t, eta_t, gsp, mop, _stream_handle(stream)), self._ctx)
+
+    def palsgd_step_sync(self, t, alpha_t, eta_t, grad_scale=None, mask_override=None, stream=None):
+        gs, gsp = _f32(grad_scale)
+        mo, mop = _u8(mask_override)
+        _check(lib().palsgd_step_sync(self._ctx, int(t), alpha_t, eta_t, gsp, mop, _stream_handle(stream)), self._ctx)
 
     def palsgd_outer_step(self, t, stream=None):
         _check(lib().palsgd_outer_step(self._ctx, int(t), _stream_handle(stream)), self._ctx)

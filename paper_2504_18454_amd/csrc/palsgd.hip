@@ -267,6 +267,73 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
     }
 }
 
+// Last local update of a window fused with the outer step (Alg. 1, step t with (t+1) mod H = 0):
+// a wavefront owns a tile of ALL K rows.  It takes the replicas in ascending order, four at a
+// time (their loads in flight together), applies each replica's branch, stores the InnerOPT
+// state, keeps the new x_k in registers only and adds x - x_k to the outer gradient; then
+// OuterOPT and the restart stores.  Against the two separate launches this saves writing the
+// K rows of X in the local update and reading them back in the outer step (8K of 34K+16 bytes
+// per element with AdamW).  Slot s of `args` is replica s.  The arithmetic, its order and its
+// roundings are those of step_kernel followed by outer_kernel_walk: results are bit-identical.
+constexpr int kSyncBatch = 4;
+
+template <int INNER, int GDT, bool TAB>
+__global__ __launch_bounds__(kWave) void sync_step_kernel(const StepArgs args, const float* __restrict__ wd_tab,
+                                                          float* __restrict__ X, float* __restrict__ M,
+                                                          float* __restrict__ V, const void* __restrict__ G,
+                                                          float* __restrict__ XG, float* __restrict__ OM,
+                                                          const float* __restrict__ clip_scale, uint64_t n,
+                                                          uint64_t row_stride, uint32_t K, Hyper h, OuterArgs a) {
+    const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
+    if (e >= n) return;
+    typedef GradLoad<GDT> GL;
+    const f4 xg = ld4(XG + e);
+    f4 om = ld4(OM + e);
+    const float wd = TAB ? wd_tab[e >> 6] : h.wd;
+    f4 dsum = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t k0 = 0; k0 < K; k0 += kSyncBatch) {
+        typename GL::raw gr[kSyncBatch];
+        f4 xv[kSyncBatch], mv[kSyncBatch], vv[kSyncBatch];
+#pragma unroll
+        for (int u = 0; u < kSyncBatch; ++u) {
+            if (k0 + u < K) {
+                const uint64_t o = (uint64_t)(k0 + u) * row_stride + e;
+                xv[u] = ld4(X + o);
+                if (!args.s[k0 + u].mix) {
+                    gr[u] = GL::load(G, o);
+                    mv[u] = ld4(M + o);
+                    if (INNER == PALSGD_INNER_ADAMW) vv[u] = ld4(V + o);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kSyncBatch; ++u) {
+            if (k0 + u < K) {
+                const Slot sl = args.s[k0 + u];
+                const uint64_t o = (uint64_t)(k0 + u) * row_stride + e;
+                if (sl.mix) {
+                    xv[u] = xv[u] - sl.beta_mix * (xv[u] - xg);
+                } else {
+                    const float gs = clip_scale ? sl.gscale * clip_scale[sl.replica] : sl.gscale;
+                    const f4 g = GL::widen(gr[u]) * gs;
+                    if (INNER == PALSGD_INNER_ADAMW) {
+                        adamw4(xv[u], mv[u], vv[u], g, h, sl.c1, sl.c2, sl.lr * wd);
+                        st4(V + o, vv[u]);
+                    } else {
+                        sgdm4(xv[u], mv[u], g, h.momentum, sl.lr, wd);
+                    }
+                    st4(M + o, mv[u]);
+                }
+                dsum += xg - xv[u];
+            }
+        }
+    }
+    const f4 xn = outer4(dsum, xg, om, a);
+    st4(XG + e, xn);
+    st4(OM + e, om);
+    for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
+}
+
 // Variant 2: a workgroup owns a tile of 4 x 256 elements.  Wave w sums the replicas
 // k = w, w+4, ... for the whole tile, the four partial sums per element meet in LDS,
 // and wave w finishes sub-tile w: fixed-order combine, OuterOPT, stores.  Puts 4*ceil(K/4)
@@ -830,10 +897,11 @@ void dispatch_step(palsgd_ctx* c, const StepArgs& args, const Slot* dev_slots, u
     else launch_step<PALSGD_INNER_SGDM, PALSGD_GRAD_F32>(c, args, dev_slots, n_slots, any_grad, clip, st);
 }
 
-// Shared body of palsgd_inner_step / palsgd_pseudo_sync / palsgd_step.
-palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alpha, float eta,
-                           const float* grad_scale, const uint8_t* mask_override, bool do_grad, bool do_mix,
-                           void* stream) {
+// Argument checks and per-slot scalars of step t for the replicas that take a requested branch.
+// Nothing is launched and no state is changed here.
+palsgd_status plan_slots(palsgd_ctx* c, const char* who, uint64_t t, float alpha, float eta, const float* grad_scale,
+                         const uint8_t* mask_override, bool do_grad, bool do_mix, StepArgs& args, uint32_t& n,
+                         bool stepped[PALSGD_MAX_K]) {
     if (!c) {
         set_error(g_error, "%s: NULL context", who);
         return PALSGD_EINVAL;
@@ -853,9 +921,8 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
     }
     const uint32_t K = c->cfg.K;
     const double p = c->cfg.p;
-    StepArgs args;
-    uint32_t n = 0;
-    bool stepped[PALSGD_MAX_K] = {false};
+    n = 0;
+    for (uint32_t k = 0; k < PALSGD_MAX_K; ++k) stepped[k] = false;
     for (uint32_t k = 0; k < K; ++k) {
         bool mix = mask_override ? mask_override[k] != 0 : draw_u24(c->cfg.seed, t, k, K) < c->draw_threshold;
         if (mix ? !do_mix : !do_grad) continue;
@@ -888,27 +955,64 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
             stepped[k] = true;
         }
     }
-    if (n == 0) return PALSGD_OK;
-    bool any_grad = false;
-    for (uint32_t k = 0; k < K; ++k) any_grad = any_grad || stepped[k];
-    if (any_grad && !c->wd_uniform && !c->d_wd_tab) {  // made by the first launch that needs it
+    return PALSGD_OK;
+}
+
+// What a launch with gradient steps needs beforehand: the weight-decay table, private InnerOPT state.
+palsgd_status prepare_gradient_launch(palsgd_ctx* c, const char* who, hipStream_t st) {
+    if (!c->wd_uniform && !c->d_wd_tab) {  // made by the first launch that needs it
         palsgd_status rc = build_wd_table(c);
         if (rc != PALSGD_OK) return rc;
     }
+    return unshare_moments(c, who, st);
+}
+
+// Shared body of palsgd_inner_step / palsgd_pseudo_sync / palsgd_step.
+palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alpha, float eta,
+                           const float* grad_scale, const uint8_t* mask_override, bool do_grad, bool do_mix,
+                           void* stream) {
+    StepArgs args;
+    uint32_t n = 0;
+    bool stepped[PALSGD_MAX_K];
+    palsgd_status rc = plan_slots(c, who, t, alpha, eta, grad_scale, mask_override, do_grad, do_mix, args, n, stepped);
+    if (rc != PALSGD_OK) return rc;
+    if (n == 0) return PALSGD_OK;
+    const uint32_t K = c->cfg.K;
+    bool any_grad = false;
+    for (uint32_t k = 0; k < K; ++k) any_grad = any_grad || stepped[k];
     hipStream_t st = (hipStream_t)stream;
     if (any_grad) {
-        palsgd_status rc = unshare_moments(c, who, st);
+        rc = prepare_gradient_launch(c, who, st);
         if (rc != PALSGD_OK) return rc;
     }
     // clipping scales computed by palsgd_clip_grad_norm are consumed by the first gradient step after it
     const float* clip = any_grad && c->clip_armed ? clip_scales(c) : nullptr;
     dispatch_step(c, args, nullptr, n, any_grad, clip, st);
-    palsgd_status rc = check_launch(c, who);
+    rc = check_launch(c, who);
     if (rc != PALSGD_OK) return rc;
     if (clip) c->clip_armed = false;
     for (uint32_t k = 0; k < K; ++k)
         if (stepped[k]) c->tau[k] += 1;
     return PALSGD_OK;
+}
+
+template <int INNER, int GDT>
+void launch_sync_step(palsgd_ctx* c, const StepArgs& args, const float* clip, const OuterArgs& a, hipStream_t st) {
+    const uint32_t K = c->cfg.K;
+    // Per batch of four replicas: their state in, their InnerOPT state out (the K+2 rows of x leave at the
+    // end). A wavefront has about half of a batch in flight at a time: measured best 6-7 for AdamW with
+    // bf16 gradients, 8-12 for SGD-momentum, which this rule gives (7 and 10).
+    const uint32_t per_batch = kSyncBatch * ((INNER == PALSGD_INNER_ADAMW ? 20u : 12u) + (GDT == PALSGD_GRAD_F32 ? 4u : 2u));
+    const uint32_t waves = c->outer_waves ? c->outer_waves : auto_waves(per_batch * kTile / 2, 6);
+    Hyper h{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum, c->wd_eff0};
+    const palsgd_buffers& b = c->buf;
+    const uint32_t lds = lds_cap(waves, 0);
+    if (c->wd_uniform)
+        sync_step_kernel<INNER, GDT, false><<<tile_count(c), kWave, lds, st>>>(args, nullptr, b.X, b.M, b.V, b.G, b.XG, b.OM,
+                                                                             clip, c->P_padded, b.row_stride, K, h, a);
+    else
+        sync_step_kernel<INNER, GDT, true><<<tile_count(c), kWave, lds, st>>>(args, c->d_wd_tab, b.X, b.M, b.V, b.G, b.XG,
+                                                                            b.OM, clip, c->P_padded, b.row_stride, K, h, a);
 }
 
 }  // namespace
@@ -1025,6 +1129,39 @@ palsgd_status palsgd_pseudo_sync(palsgd_ctx* ctx, uint64_t t, float alpha_t, flo
 palsgd_status palsgd_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, float eta_t, const float* grad_scale,
                           const uint8_t* mask_override, void* stream) {
     return local_update(ctx, "palsgd_step", t, alpha_t, eta_t, grad_scale, mask_override, true, true, stream);
+}
+
+palsgd_status palsgd_step_sync(palsgd_ctx* ctx, uint64_t t, float alpha_t, float eta_t, const float* grad_scale,
+                               const uint8_t* mask_override, void* stream) {
+    StepArgs args;
+    uint32_t n = 0;
+    bool stepped[PALSGD_MAX_K];
+    palsgd_status rc =
+        plan_slots(ctx, "palsgd_step_sync", t, alpha_t, eta_t, grad_scale, mask_override, true, true, args, n, stepped);
+    if (rc != PALSGD_OK) return rc;
+    const uint32_t K = ctx->cfg.K;  // both branches requested: n == K and slot s is replica s
+    bool any_grad = false;
+    for (uint32_t k = 0; k < K; ++k) any_grad = any_grad || stepped[k];
+    hipStream_t st = (hipStream_t)stream;
+    if (any_grad) {
+        rc = prepare_gradient_launch(ctx, "palsgd_step_sync", st);
+        if (rc != PALSGD_OK) return rc;
+    }
+    const float* clip = any_grad && ctx->clip_armed ? clip_scales(ctx) : nullptr;
+    OuterArgs a{(float)(1.0 / (double)K), ctx->cfg.outer_lr, ctx->cfg.outer_momentum, ctx->cfg.outer_nesterov ? 1 : 0};
+    const bool adamw = ctx->cfg.inner == PALSGD_INNER_ADAMW, bf16 = ctx->cfg.grad_dtype == PALSGD_GRAD_BF16;
+    if (adamw && bf16) launch_sync_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16>(ctx, args, clip, a, st);
+    else if (adamw) launch_sync_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_F32>(ctx, args, clip, a, st);
+    else if (bf16) launch_sync_step<PALSGD_INNER_SGDM, PALSGD_GRAD_BF16>(ctx, args, clip, a, st);
+    else launch_sync_step<PALSGD_INNER_SGDM, PALSGD_GRAD_F32>(ctx, args, clip, a, st);
+    rc = check_launch(ctx, "palsgd_step_sync");
+    if (rc != PALSGD_OK) return rc;
+    if (clip) ctx->clip_armed = false;
+    for (uint32_t k = 0; k < K; ++k)
+        if (stepped[k]) ctx->tau[k] += 1;
+    ctx->n_outer += 1;
+    ctx->last_outer_t = t;
+    return PALSGD_OK;
 }
 
 static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, float* diag_out_dev, void* stream) {

@@ -135,7 +135,8 @@ class Run:
         for k in range(K):
             self.G[k].index_copy_(0, self.idx_dev, gd[k])
 
-    def iterate(self, steps, *, fused=True, grad_scale=None, mask_fn=None, check_every=0, clip=None, diag_outer=False):
+    def iterate(self, steps, *, fused=True, grad_scale=None, mask_fn=None, check_every=0, clip=None, diag_outer=False,
+                fused_sync=False):
         for _ in range(steps):
             t = self.t
             self.make_gradients()
@@ -162,6 +163,11 @@ class Run:
                 mask_o, synced = self.ora.iteration(t, self.alpha, self.eta, grad_scale=gs64, mask_override=mo)
             if mo is None:
                 assert np.array_equal(self.lib.palsgd_draw(t), mask_o), f"draws differ at t={t}"
+            if fused_sync and (t + 1) % self.H == 0:   # local update and outer step of a sync step in one launch
+                assert synced
+                self.lib.palsgd_step_sync(t, self.alpha, self.eta, grad_scale, mo)
+                self.t += 1
+                continue
             if fused:
                 self.lib.palsgd_step(t, self.alpha, self.eta, grad_scale, mo)
             else:                          # the two branches as separate calls, mixing first

@@ -300,3 +300,30 @@ def test_c_abi_from_plain_c():
     out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     print(out.stdout.strip())
     assert out.returncode == 0 and "PASS" in out.stdout, (out.returncode, out.stdout, out.stderr)
+
+
+@pytest.mark.parametrize("inner,grad_dtype,K", [("adamw", "f32", 3), ("adamw", "bf16", 8), ("sgdm", "f32", 5),
+                                               ("sgdm", "bf16", 1), ("adamw", "bf16", 64), ("adamw", "f32", 6)])
+def test_fused_sync_step_equals_step_plus_outer(inner, grad_dtype, K):
+    """palsgd_step_sync (local update + outer step of a synchronisation step in one launch) against the oracle,
+    and bit for bit against the two separate launches."""
+    kw = dict(K=K, numels=RAGGED, inner=inner, grad_dtype=grad_dtype, p=0.3, H=3, seed=26 + K, sigma=0.05,
+              wd_mult=[1, 0, 1, 1, 0.5, 1, 0], row_extra=1)
+    a, b = _run(**kw), _run(**kw)
+    gs = [0.5 + 0.1 * (k % 5) for k in range(K)]
+    a.iterate(10, fused_sync=True, grad_scale=gs)
+    b.iterate(10, fused_sync=False, grad_scale=gs)
+    a.compare(); b.compare()
+    for ta, tb in ((a.X, b.X), (a.M, b.M), (a.XG, b.XG), (a.OM, b.OM)) + (((a.V, b.V),) if a.V is not None else ()):
+        assert torch.equal(ta, tb)
+    a.close(); b.close()
+
+
+def test_config_gptneo125m_k8_fused_sync_sampled():
+    """The benchmark configuration with the fused synchronisation step, 130 steps (two synchronisations)."""
+    w = workload("gptneo125m_k8")
+    r = _run(K=w.K, numels=w.numels, inner=w.inner, grad_dtype=w.grad_dtype, p=w.p, H=w.H, alpha=w.alpha, eta=w.eta,
+             sigma=w.sigma, seed=w.seed, per_edge=256, n_random=1 << 16)
+    r.iterate(130, fused_sync=True)
+    print("worst err/bound", r.compare())
+    r.close()
