@@ -29,7 +29,7 @@ def _load():
                                    C.c_uint64, C.c_double, C.c_double, C.c_double, C.c_double,
                                    C.c_double, C.c_uint64, C.c_double]
         _lib.ora_sgdm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_uint64,
-                                  C.c_double, C.c_double, C.c_double, C.c_double]
+                                  C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
         _lib.ora_outer.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p,
                                    C.c_uint64, C.c_double, C.c_double, C.c_int]
         _lib.ora_local_step.argtypes = [C.c_void_p, C.c_uint64, C.c_double, C.c_double,
@@ -90,10 +90,10 @@ def adamw(x, m, v, g, lr, beta1, beta2, eps, wd, tau, grad_scale=1.0):
                       int(tau), float(grad_scale))
 
 
-def sgdm(x, buf, g, lr, momentum, wd, grad_scale=1.0):
+def sgdm(x, buf, g, lr, momentum, wd, grad_scale=1.0, nesterov=False):
     gp, gd = _gptr(g)
     _load().ora_sgdm(_ptr(x, np.float32), _ptr(buf, np.float32), gp, gd, x.size, float(lr),
-                     float(momentum), float(wd), float(grad_scale))
+                     float(momentum), float(wd), float(grad_scale), int(bool(nesterov)))
 
 
 def outer(X, xg, om, lr_o, mu_o, nesterov):
@@ -137,7 +137,8 @@ class _CState(C.Structure):
         ("tensor_wd_mult", C.c_void_p),
         ("inner", C.c_int), ("g_dtype", C.c_int),
         ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
-        ("weight_decay", C.c_double), ("momentum", C.c_double), ("p", C.c_double),
+        ("weight_decay", C.c_double), ("momentum", C.c_double), ("inner_nesterov", C.c_int),
+        ("p", C.c_double),
         ("H", C.c_uint32), ("outer_lr", C.c_double), ("outer_momentum", C.c_double),
         ("outer_nesterov", C.c_int), ("seed", C.c_uint64),
         ("X", C.c_void_p), ("M", C.c_void_p), ("V", C.c_void_p), ("G", C.c_void_p),
@@ -156,7 +157,8 @@ class OracleState:
 
     def __init__(self, K, x0, tensor_offset, tensor_numel, *, inner="adamw", grad_dtype="f32",
                  beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, momentum=0.9, p=0.1, H=16,
-                 outer_lr=0.2, outer_momentum=0.9, outer_nesterov=True, seed=0, wd_mult=None):
+                 outer_lr=0.2, outer_momentum=0.9, outer_nesterov=True, seed=0, wd_mult=None,
+                 inner_nesterov=False):
         self.lib = _load()
         x0 = np.ascontiguousarray(x0, dtype=np.float32)
         row = x0.size
@@ -184,6 +186,7 @@ class OracleState:
         s.g_dtype = 0 if grad_dtype == "f32" else 1
         s.beta1, s.beta2, s.eps = f32(beta1), f32(beta2), f32(eps)
         s.weight_decay, s.momentum = f32(weight_decay), f32(momentum)
+        s.inner_nesterov = int(bool(inner_nesterov))
         s.p, s.H = float(p), int(H)
         s.outer_lr, s.outer_momentum = f32(outer_lr), f32(outer_momentum)
         s.outer_nesterov = int(bool(outer_nesterov))

@@ -155,10 +155,12 @@ void ora_adamw(float *x, float *m, float *v, const void *g, int g_dtype,
 /* into the gradient:                                                         */
 /*   d = g + wd x      buf <- mu buf + d      x <- x - lr buf                 */
 /* (buf starts at 0, so the first step gives buf = d).  mu = 0 is plain SGD,  */
-/* the InnerOPT of the paper's Theorem 1.                                     */
+/* the InnerOPT of the paper's Theorem 1.  With nesterov != 0 the step looks  */
+/* ahead along the momentum (Sutskever et al. 2013, the form the optimizer    */
+/* comparison of App. C varies):   x <- x - lr (d + mu buf).                  */
 /* ------------------------------------------------------------------------- */
 void ora_sgdm(float *x, float *buf, const void *g, int g_dtype, uint64_t n,
-              double lr, double momentum, double wd, double grad_scale)
+              double lr, double momentum, double wd, double grad_scale, int nesterov)
 {
     int64_t i;
 #pragma omp parallel for schedule(static) num_threads(g_threads)
@@ -167,7 +169,7 @@ void ora_sgdm(float *x, float *buf, const void *g, int g_dtype, uint64_t n,
         double d = grad_scale * grad_at(g, g_dtype, (uint64_t)i) + wd * xi;
         double bi = momentum * (double)buf[i] + d;
         buf[i] = (float)bi;
-        x[i] = (float)(xi - lr * bi);
+        x[i] = (float)(xi - lr * (nesterov ? d + momentum * bi : bi));
     }
 }
 
@@ -223,6 +225,7 @@ typedef struct {
     int g_dtype;             /* 0 fp32, 1 bf16                                */
     double beta1, beta2, eps, weight_decay; /* AdamW (weight_decay also SGDM) */
     double momentum;         /* SGDM                                          */
+    int inner_nesterov;      /* SGDM: Nesterov form of the momentum step      */
     double p;                /* mixing probability                            */
     uint32_t H;              /* sync interval                                 */
     double outer_lr, outer_momentum;
@@ -276,7 +279,7 @@ void ora_local_step(ora_state *s, uint64_t t, double alpha_t, double eta_t,
                 } else {
                     float *bk = s->M + (uint64_t)k * s->row_stride;
                     ora_sgdm(xk + off, bk + off, gk, s->g_dtype, len, lr,
-                             s->momentum, wd, gs);
+                             s->momentum, wd, gs, s->inner_nesterov);
                 }
             }
         }
@@ -338,7 +341,8 @@ void ora_ddp_step(ora_state *s, double alpha_t, const double *grad_scale)
             ora_adamw(s->XG + off, s->M + off, s->V + off, gbar + off, 2, len, alpha_t, s->beta1,
                       s->beta2, s->eps, wd, s->tau[0], 1.0);
         else
-            ora_sgdm(s->XG + off, s->M + off, gbar + off, 2, len, alpha_t, s->momentum, wd, 1.0);
+            ora_sgdm(s->XG + off, s->M + off, gbar + off, 2, len, alpha_t, s->momentum, wd, 1.0,
+                     s->inner_nesterov);
     }
     for (uint32_t k = 0; k < s->K; ++k) {
         memcpy(s->X + (uint64_t)k * s->row_stride, s->XG, sizeof(float) * n);

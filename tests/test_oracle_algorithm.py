@@ -90,8 +90,12 @@ class BruteForce:
                         x = self.x[k][i] * (1 - lr * wd) - step_size * m / denom
                         self.m[k][i], self.v[k][i], self.x[k][i] = self.r(m), self.r(v), self.r(x)
                     else:
-                        buf = hp["mu"] * self.m[k][i] + g + wd * self.x[k][i]
-                        self.x[k][i] = self.r(self.x[k][i] - lr * buf)
+                        d = g + wd * self.x[k][i]
+                        buf = hp["mu"] * self.m[k][i] + d
+                        if hp.get("inner_nesterov"):       # look-ahead: step along d + mu * (new buffer)
+                            self.x[k][i] = self.r(self.x[k][i] - lr * d - lr * hp["mu"] * buf)
+                        else:
+                            self.x[k][i] = self.r(self.x[k][i] - lr * buf)
                         self.m[k][i] = self.r(buf)
         if (t + 1) % hp["H"] == 0:
             for i in range(len(self.xg)):
@@ -107,18 +111,21 @@ class BruteForce:
 @pytest.mark.parametrize("K,H,numels,inner,nesterov", [
     (1, 1, [1], "adamw", True), (2, 2, [1], "sgdm", True), (2, 3, [3], "adamw", False),
     (3, 2, [5, 17], "adamw", True), (3, 3, [17, 1, 3], "sgdm", False), (2, 1, [5], "sgdm", True),
+    (3, 2, [3, 5], "sgdm_nesterov", True),
 ])
 def test_brute_force_tiny(oracle_mod, K, H, numels, inner, nesterov):
+    inner_nesterov = inner.endswith("_nesterov")
+    inner = inner.split("_")[0]
     rng = np.random.default_rng(100 + K * 7 + H)
     offs, row = flat_layout(numels)
     x0 = _padded(rng, numels)
     wdm = [1.0, 0.0, 2.0][:len(numels)]
     hp = dict(p=0.3, H=H, b1=F(0.9), b2=F(0.999), eps=F(1e-8), wd=F(0.05), mu=F(0.8),
-              lr_o=F(0.7), mu_o=F(0.9), nesterov=nesterov)
+              lr_o=F(0.7), mu_o=F(0.9), nesterov=nesterov, inner_nesterov=inner_nesterov)
     seed = 99
     st = _state(oracle_mod, K, x0, numels, inner=inner, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.05,
                 momentum=0.8, p=0.3, H=H, outer_lr=0.7, outer_momentum=0.9, outer_nesterov=nesterov,
-                seed=seed, wd_mult=wdm)
+                seed=seed, wd_mult=wdm, inner_nesterov=inner_nesterov)
     bf = BruteForce(K, x0, numels, wdm, inner, hp, seed)
     alpha, eta = F(0.01), F(4.0)
     mixed = 0

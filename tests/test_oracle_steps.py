@@ -154,20 +154,23 @@ def test_adamw_zero_padding_stays_zero(oracle_mod):
 
 
 # ---------------------------------------------------------------------------- SGDM
+@pytest.mark.parametrize("nesterov", [False, True])
 @pytest.mark.parametrize("mu,wd", [(0.0, 0.0), (float(f32(0.9)), 0.0), (float(f32(0.9)), float(f32(1e-4))),
                                    (float(f32(0.5)), float(f32(0.05)))])
-def test_sgdm_matches_library_float64(oracle_mod, mu, wd):
+def test_sgdm_matches_library_float64(oracle_mod, mu, wd, nesterov):
+    if nesterov and not mu:
+        pytest.skip("the library routine refuses the Nesterov form without momentum")
     rng = np.random.default_rng(5)
     n, steps, lr = 4096, 10, 1e-3 / (1 - 0.1)
     x0 = rng.standard_normal(n).astype(f32)
     grads = rng.standard_normal((steps, n)).astype(f32)
     p = torch.nn.Parameter(torch.tensor(x0, dtype=torch.float64))
-    opt = torch.optim.SGD([p], lr=lr, momentum=mu, weight_decay=wd)
+    opt = torch.optim.SGD([p], lr=lr, momentum=mu, weight_decay=wd, nesterov=nesterov)
     x = x0.copy(); buf = np.zeros(n, f32)
     for s in range(steps):
         p.grad = torch.tensor(grads[s], dtype=torch.float64)
         opt.step()
-        oracle_mod.sgdm(x, buf, grads[s], lr, mu, wd)
+        oracle_mod.sgdm(x, buf, grads[s], lr, mu, wd, nesterov=nesterov)
         _near_bit_exact(x, p.detach().numpy())
         with torch.no_grad():
             p.copy_(p.float().double())
@@ -177,6 +180,23 @@ def test_sgdm_matches_library_float64(oracle_mod, mu, wd):
                 b.copy_(b.float().double())
                 buf = b.numpy().astype(f32)
         x = p.detach().numpy().astype(f32)
+
+
+def test_sgdm_two_steps_by_hand(oracle_mod):
+    # mu = 0.5, lr = 0.125, g = 1, no decay, from x = 0 (all exactly representable):
+    # heavy ball: buf 1, 1.5 -> x = -0.125, -0.3125
+    # Nesterov:   steps 1 + 0.5*1 = 1.5 and 1 + 0.5*1.5 = 1.75 -> x = -0.1875, -0.40625
+    for nesterov, want in ((False, (-0.125, -0.3125)), (True, (-0.1875, -0.40625))):
+        x = np.zeros(64, f32); buf = np.zeros(64, f32); g = np.ones(64, f32)
+        for s in range(2):
+            oracle_mod.sgdm(x, buf, g, 0.125, 0.5, 0.0, nesterov=nesterov)
+            assert (x == f32(want[s])).all() and (buf == f32((1.0, 1.5)[s])).all()
+    # without momentum both forms are plain SGD
+    xa = np.zeros(64, f32); xb = np.zeros(64, f32); ba = np.zeros(64, f32); bb = np.zeros(64, f32)
+    g = np.linspace(-1, 1, 64).astype(f32)
+    oracle_mod.sgdm(xa, ba, g, 0.3, 0.0, 0.0, nesterov=False)
+    oracle_mod.sgdm(xb, bb, g, 0.3, 0.0, 0.0, nesterov=True)
+    assert (xa == xb).all() and (xa == (-np.float64(0.3) * g).astype(f32)).all()
 
 
 def test_plain_sgd_on_quadratic_closed_form(oracle_mod):
