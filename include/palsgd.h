@@ -70,7 +70,10 @@ typedef struct {
     int32_t grad_dtype;           /* palsgd_grad_dtype                                      */
     float beta1, beta2, eps;      /* AdamW moments and epsilon                              */
     float weight_decay;           /* AdamW: decoupled; SGDM: added to the gradient          */
-    float momentum;               /* SGDM momentum (dampening 0, not Nesterov)              */
+    float momentum;               /* SGDM momentum (dampening 0)                            */
+    int32_t inner_nesterov;       /* SGDM: 1 = Nesterov form x -= lr (d + mu buf), 0 = heavy
+                                     ball x -= lr buf (the optimizer comparison of App. C);
+                                     ignored by AdamW                                       */
     double p;                     /* mixing probability, 0 <= p < 1 (Alg. 1 input)          */
     uint32_t H;                   /* synchronization interval, >= 1 (Alg. 1 input)          */
     float outer_lr;               /* OuterOPT learning rate                                 */

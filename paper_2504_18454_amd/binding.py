@@ -40,7 +40,7 @@ class Config(C.Structure):
                 ("tensor_numel", C.POINTER(C.c_uint64)), ("tensor_wd_mult", C.POINTER(C.c_float)),
                 ("inner", C.c_int32), ("grad_dtype", C.c_int32),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("weight_decay", C.c_float), ("momentum", C.c_float),
+                ("weight_decay", C.c_float), ("momentum", C.c_float), ("inner_nesterov", C.c_int32),
                 ("p", C.c_double), ("H", C.c_uint32),
                 ("outer_lr", C.c_float), ("outer_momentum", C.c_float), ("outer_nesterov", C.c_int32),
                 ("seed", C.c_uint64)]
@@ -115,7 +115,7 @@ def make_config(K: int, tensor_numel: Sequence[int], *, inner: str = "adamw", gr
                 beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.01,
                 momentum: float = 0.9, p: float = 0.1, H: int = 16, outer_lr: float = 0.2,
                 outer_momentum: float = 0.9, outer_nesterov: bool = True, seed: int = 0,
-                wd_mult: Optional[Sequence[float]] = None) -> Config:
+                wd_mult: Optional[Sequence[float]] = None, inner_nesterov: bool = False) -> Config:
     cfg = Config()
     n = len(tensor_numel)
     numel = (C.c_uint64 * max(n, 1))(*[int(v) for v in tensor_numel])
@@ -130,6 +130,7 @@ def make_config(K: int, tensor_numel: Sequence[int], *, inner: str = "adamw", gr
     cfg.grad_dtype = GRAD[grad_dtype] if isinstance(grad_dtype, str) else int(grad_dtype)
     cfg.beta1, cfg.beta2, cfg.eps = beta1, beta2, eps
     cfg.weight_decay, cfg.momentum = weight_decay, momentum
+    cfg.inner_nesterov = int(bool(inner_nesterov))
     cfg.p, cfg.H = float(p), int(H)
     cfg.outer_lr, cfg.outer_momentum, cfg.outer_nesterov = outer_lr, outer_momentum, int(bool(outer_nesterov))
     cfg.seed = int(seed) & (2 ** 64 - 1)

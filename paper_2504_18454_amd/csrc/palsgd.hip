@@ -73,6 +73,7 @@ struct StepArgs {
 struct Hyper {
     float beta1, beta2, eps, momentum;
     float wd;        // weight decay when every tensor has the same multiplier
+    int nesterov;    // SGD-momentum: step along d + mu * buf instead of buf
 };
 
 __device__ __forceinline__ f4 ld4(const float* p) { return __builtin_nontemporal_load((const f4*)p); }
@@ -128,13 +129,15 @@ __device__ __forceinline__ void adamw4(f4& x, f4& m, f4& v, f4 g, const Hyper& h
     }
 }
 
-// SGD with momentum on four elements: d = g + wd x; buf = mu buf + d; x -= lr buf.
-__device__ __forceinline__ void sgdm4(f4& x, f4& b, f4 g, float mu, float lr, float wd) {
+// SGD with momentum on four elements: d = g + wd x; buf = mu buf + d; x -= lr buf, or in the
+// Nesterov form x -= lr (d + mu buf).
+__device__ __forceinline__ void sgdm4(f4& x, f4& b, f4 g, const Hyper& h, float lr, float wd) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         float d = fmaf(wd, x[i], g[i]);
-        float bi = fmaf(mu, b[i], d);
-        x[i] = fmaf(-lr, bi, x[i]);
+        float bi = fmaf(h.momentum, b[i], d);
+        float dir = h.nesterov ? fmaf(h.momentum, bi, d) : bi;
+        x[i] = fmaf(-lr, dir, x[i]);
         b[i] = bi;
     }
 }
@@ -193,7 +196,7 @@ __global__ __launch_bounds__(kWave) void step_kernel(const StepArgs args, const 
         st4(V + o, vv);
     } else {
         f4 g = GL::widen(gr) * gs;
-        sgdm4(xv, mv, g, h.momentum, sl.lr, wd);
+        sgdm4(xv, mv, g, h, sl.lr, wd);
         st4(X + o, xv);
         st4(M + o, mv);
     }
@@ -320,7 +323,7 @@ __global__ __launch_bounds__(kWave) void sync_step_kernel(const StepArgs args, c
                         adamw4(xv[u], mv[u], vv[u], g, h, sl.c1, sl.c2, sl.lr * wd);
                         st4(V + o, vv[u]);
                     } else {
-                        sgdm4(xv[u], mv[u], g, h.momentum, sl.lr, wd);
+                        sgdm4(xv[u], mv[u], g, h, sl.lr, wd);
                     }
                     st4(M + o, mv[u]);
                 }
@@ -503,7 +506,7 @@ __global__ __launch_bounds__(kWave) void ddp_kernel(const DdpArgs a, const float
     if (INNER == PALSGD_INNER_ADAMW)
         adamw4(xv, mv, vv, g, h, a.c1, a.c2, a.lr * wd);
     else
-        sgdm4(xv, mv, g, h.momentum, a.lr, wd);
+        sgdm4(xv, mv, g, h, a.lr, wd);
     st4(XG + e, xv);
     st4(M + e, mv);  // the common InnerOPT state lives in replica 0 during the warm-up
     if (INNER == PALSGD_INNER_ADAMW) st4(V + e, vv);
@@ -811,6 +814,10 @@ uint32_t auto_waves(uint32_t bytes_per_wave, uint32_t floor_waves = 3) {
     return w < floor_waves ? floor_waves : (w > 32 ? 32 : w);
 }
 
+Hyper hyper_of(const palsgd_ctx* c) {
+    return Hyper{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum, c->wd_eff0, c->cfg.inner_nesterov != 0};
+}
+
 palsgd_status check_launch(palsgd_ctx* c, const char* what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -860,7 +867,7 @@ void launch_step(palsgd_ctx* c, const StepArgs& args, const Slot* dev_slots, uin
                                        : 24u;
     const uint32_t waves = c->step_waves ? c->step_waves : auto_waves(per_elem * kTile);
     dim3 grid(tiles, n_slots), block(kWave);
-    Hyper h{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum, c->wd_eff0};
+    Hyper h = hyper_of(c);
     const uint32_t lds = lds_cap(waves, 0);
     const palsgd_buffers& b = c->buf;
 #define PALSGD_STEP(TAB, DEV, tab)                                                                              \
@@ -1004,7 +1011,7 @@ void launch_sync_step(palsgd_ctx* c, const StepArgs& args, const float* clip, co
     // bf16 gradients, 8-12 for SGD-momentum, which this rule gives (7 and 10).
     const uint32_t per_batch = kSyncBatch * ((INNER == PALSGD_INNER_ADAMW ? 20u : 12u) + (GDT == PALSGD_GRAD_F32 ? 4u : 2u));
     const uint32_t waves = c->outer_waves ? c->outer_waves : auto_waves(per_batch * kTile / 2, 6);
-    Hyper h{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum, c->wd_eff0};
+    Hyper h = hyper_of(c);
     const palsgd_buffers& b = c->buf;
     const uint32_t lds = lds_cap(waves, 0);
     if (c->wd_uniform)
@@ -1262,7 +1269,7 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
     const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
     const uint32_t per_elem = (adamw ? 24u : 16u) + 4u * K + K * (bf16 ? 2u : 4u);
     const uint32_t lds = lds_cap(ctx->outer_waves ? ctx->outer_waves : auto_waves(per_elem * kTile, 4), 0);
-    Hyper h{ctx->cfg.beta1, ctx->cfg.beta2, ctx->cfg.eps, ctx->cfg.momentum, ctx->wd_eff0};
+    Hyper h = hyper_of(ctx);
     hipStream_t st = (hipStream_t)stream;
     const palsgd_buffers& b = ctx->buf;
     const float* clip = ctx->clip_mean_armed ? mean_clip_scale(ctx) : nullptr;

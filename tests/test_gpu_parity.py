@@ -58,6 +58,23 @@ def test_replica_counts(K):
     r.close()
 
 
+@pytest.mark.parametrize("grad_dtype,K,wd_mult", [("f32", 3, None), ("bf16", 8, [1, 0, 1, 1, 0.5, 1, 0])])
+def test_inner_nesterov_momentum(grad_dtype, K, wd_mult):
+    """SGD-momentum InnerOPT in its Nesterov form (App. C compares the optimizer pairs) through every kernel that
+    applies InnerOPT: DDP warm-up, local update, fused synchronisation step."""
+    kw = dict(K=K, numels=RAGGED, inner="sgdm", grad_dtype=grad_dtype, p=0.3, H=3, seed=40 + K, sigma=0.05,
+              weight_decay=1e-4, momentum=0.9, inner_nesterov=True, wd_mult=wd_mult, row_extra=1)
+    r = _run(**kw)
+    r.ddp_iterate(3)
+    r.iterate(6, check_every=1)
+    r.iterate(6, fused_sync=True)
+    r.compare()
+    h = _run(**dict(kw, inner_nesterov=False))          # the heavy-ball form is a different trajectory
+    h.ddp_iterate(3); h.iterate(12)
+    assert not torch.equal(h.X, r.X)
+    r.close(); h.close()
+
+
 @pytest.mark.parametrize("variant,step_waves,outer_waves", [(1, 3, 3), (2, 32, 4), (1, 0, 32), (2, 11, 0), (2, 5, 8)])
 def test_tuning_shapes_agree_with_oracle(variant, step_waves, outer_waves):
     r = _run(K=6, numels=[100000, 64, 777, 40000], inner="adamw", grad_dtype="bf16", p=0.2, H=3, seed=15,
