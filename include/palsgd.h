@@ -99,8 +99,11 @@ palsgd_status palsgd_layout(const palsgd_config *cfg, uint64_t *P_padded, uint64
  * (device, P_padded floats, padding zero) is not NULL, it is copied into XG and every
  * row of X, and M, V, OM are cleared, on `stream`; if NULL the buffers are taken as
  * they are (resume).  EINVAL: K outside 1..64, H == 0, p outside [0,1), NULL or
- * misaligned buffers, row_stride < P_padded or not a multiple of 64, beta/eps/momentum
- * outside their ranges, V == NULL with AdamW.  On failure *out is NULL. */
+ * misaligned buffers, row_stride < P_padded or not a multiple of 64, P_padded > 2^38,
+ * beta/eps/momentum outside their ranges, V == NULL with AdamW.  When the weight-decay
+ * multipliers differ between tensors (and weight_decay != 0) a device table of one float
+ * per 64 row elements is allocated and filled here (ENOMEM / EHIP if that fails), so
+ * that no later call allocates on the step path.  On failure *out is NULL. */
 palsgd_status palsgd_init(const palsgd_config *cfg, const palsgd_buffers *buf, const float *x0_dev,
                           void *stream, palsgd_ctx **out);
 

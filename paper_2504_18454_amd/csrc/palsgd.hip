@@ -55,6 +55,7 @@ constexpr int kTile = kWave * 4;     // elements a wavefront covers with one 16-
 constexpr int kThreads = 256;        // workgroup of the LDS-staged outer variant and of init
 constexpr uint32_t kLdsPerCUDefault = 160u * 1024u;  // gfx950; the device is asked at the first launch
 constexpr uint32_t kInflightDefault = 72u * 1024u;  // bytes of loads+stores in flight per CU
+constexpr uint64_t kMaxRow = 1ull << 38;             // keeps every grid dimension below 2^31
 
 // Per-launch, per-slot scalars; slot s of the grid's y dimension works on row `replica`.
 struct Slot {
@@ -965,12 +966,8 @@ palsgd_status plan_slots(palsgd_ctx* c, const char* who, uint64_t t, float alpha
     return PALSGD_OK;
 }
 
-// What a launch with gradient steps needs beforehand: the weight-decay table, private InnerOPT state.
+// What a launch with gradient steps needs beforehand: every replica's own InnerOPT state.
 palsgd_status prepare_gradient_launch(palsgd_ctx* c, const char* who, hipStream_t st) {
-    if (!c->wd_uniform && !c->d_wd_tab) {  // made by the first launch that needs it
-        palsgd_status rc = build_wd_table(c);
-        if (rc != PALSGD_OK) return rc;
-    }
     return unshare_moments(c, who, st);
 }
 
@@ -1074,6 +1071,7 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
                    "device buffers must be 16-byte aligned");
     PALSGD_REQUIRE(buf->row_stride >= P_padded && buf->row_stride % 64 == 0,
                    "row_stride must be a multiple of 64 and >= the padded row length");
+    PALSGD_REQUIRE(P_padded <= kMaxRow, "a row may hold at most 2^38 elements (one 256-element tile per workgroup)");
     if (cfg->tensor_wd_mult)
         for (uint32_t j = 0; j < cfg->n_tensors; ++j)
             PALSGD_REQUIRE(std::isfinite(cfg->tensor_wd_mult[j]) && cfg->tensor_wd_mult[j] >= 0.0f,
@@ -1095,8 +1093,17 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
     c->cfg.tensor_wd_mult = nullptr;
     c->P_padded = P_padded;
     for (float m : c->wd_mult) c->wd_uniform = c->wd_uniform && m == c->wd_mult[0];
+    if (cfg->weight_decay == 0.0f) c->wd_uniform = true;  // the multipliers multiply zero
     c->wd_eff0 = (float)((double)cfg->weight_decay * (double)c->wd_mult[0]);
     c->draw_threshold = (uint32_t)std::floor(cfg->p * 16777216.0);
+    if (!c->wd_uniform) {  // here, not at first use: a step may be the first call inside a stream capture
+        rc = build_wd_table(c);
+        if (rc != PALSGD_OK) {
+            memcpy(g_error, c->error, sizeof g_error);
+            palsgd_destroy(c);
+            return rc;
+        }
+    }
     if (x0_dev) {
         uint64_t n4 = P_padded / 4;
         uint32_t blocks = (uint32_t)((n4 + kThreads - 1) / kThreads);
@@ -1261,10 +1268,6 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
         a.c1 = (float)((double)alpha_t / (1.0 - std::pow((double)ctx->cfg.beta1, tau)));
         a.c2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)ctx->cfg.beta2, tau)));
     }
-    if (!ctx->wd_uniform && !ctx->d_wd_tab) {
-        palsgd_status rc = build_wd_table(ctx);
-        if (rc != PALSGD_OK) return rc;
-    }
     const uint64_t n = ctx->P_padded;
     const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
     const uint32_t per_elem = (adamw ? 24u : 16u) + 4u * K + K * (bf16 ? 2u : 4u);
@@ -1401,10 +1404,6 @@ palsgd_status palsgd_capturable_begin(palsgd_ctx* ctx, uint64_t t0, void* stream
             set_error(ctx->error, "hipMalloc(device schedule): %s", hipGetErrorString(e));
             return PALSGD_ENOMEM;
         }
-    }
-    if (!ctx->wd_uniform && !ctx->d_wd_tab) {  // nothing may be allocated once a capture is running
-        palsgd_status rc = build_wd_table(ctx);
-        if (rc != PALSGD_OK) return rc;
     }
     (void)lds_per_cu();
     {

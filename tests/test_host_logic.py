@@ -67,6 +67,10 @@ def test_init_rejects_bad_arguments_without_touching_the_device():
         assert st == binding.PALSGD_EINVAL, case
         assert not out.value
         assert b"palsgd_init" in lib().palsgd_last_error(None)
+    # a row longer than the launch grids can cover
+    cfg = make_config(2, [2 ** 38 + 1])
+    st, out = _init(cfg)
+    assert st == binding.PALSGD_EINVAL and not out.value and b"2^38" in lib().palsgd_last_error(None)
     # empty model and zero-sized tensor
     for numels in ([], [5, 0]):
         cfg = make_config(2, numels)
