@@ -55,7 +55,6 @@ constexpr int kTile = kWave * 4;     // elements a wavefront covers with one 16-
 constexpr int kThreads = 256;        // workgroup of the LDS-staged outer variant and of init
 constexpr uint32_t kLdsPerCUDefault = 160u * 1024u;  // gfx950; the device is asked at the first launch
 constexpr uint32_t kInflightDefault = 72u * 1024u;  // bytes of loads+stores in flight per CU
-constexpr uint64_t kMaxRow = 1ull << 38;             // keeps every grid dimension below 2^31
 
 // Per-launch, per-slot scalars; slot s of the grid's y dimension works on row `replica`.
 struct Slot {
@@ -734,6 +733,8 @@ struct palsgd_ctx {
 };
 
 namespace {
+
+constexpr uint64_t kMaxRow = 1ull << 38;  // keeps every grid dimension below 2^31
 
 palsgd_status layout_impl(uint32_t n_tensors, const uint64_t* numel, uint64_t* P_padded, uint64_t* offs,
                           char* err) {
