@@ -257,3 +257,117 @@ class Run:
 
     def close(self):
         self.lib.palsgd_destroy()
+
+
+class PeriodicRun:
+    """A full-size run in which EVERY element is checked, not a sample.
+
+    All inputs repeat along a row with period B (x0, the quadratic's target, the gradient noise), and the
+    weight decay is uniform, so position i of a row must follow the oracle's trajectory of position i mod B:
+    the update is element-wise.  The oracle runs on one period (K rows of B elements); the device runs the
+    full-size buffers in the launch configuration of the benchmark; the comparison covers all K * row
+    elements of X, M, V and all of XG, OM, to the same tolerance as everywhere else.  Padding between
+    tensors holds zeros in x0 and in the gradients and must still be exactly zero at the end.
+    The gradients are closed-loop on the oracle's side: g = (x_k - c) + sigma * noise from the oracle's x_k.
+    """
+
+    def __init__(self, K, numels, *, B=1 << 16, inner="adamw", grad_dtype="f32", p=0.1, H=16, alpha=1e-3, eta=16.0,
+                 sigma=0.01, seed=0, device="cuda:0", **hyper):
+        self.K, self.B, self.grad_dtype = K, B, grad_dtype
+        self.p, self.H, self.alpha, self.eta, self.sigma = p, H, alpha, eta, sigma
+        self.dev = torch.device(device)
+        self.cfg = make_config(K, numels, inner=inner, grad_dtype=grad_dtype, p=p, H=H, seed=seed, **hyper)
+        self.row, offsets = palsgd_layout(self.cfg)
+        self.reps, self.tail = divmod(self.row, B)
+        self.rng = np.random.default_rng(seed + 2)
+        x0_b = (np.float32(0.02) * self.rng.standard_normal(B, dtype=np.float32)).astype(np.float32)
+        self.c_b = self.rng.standard_normal(B, dtype=np.float32)
+        pad = torch.ones(self.row, dtype=torch.bool, device=self.dev)
+        for o, n in zip(offsets, numels):
+            pad[o:o + n] = False
+        self.pad_idx = pad.nonzero().flatten()
+        del pad
+        f = torch.float32
+        x0 = torch.empty(self.row, dtype=f, device=self.dev)
+        self.tile_into(x0, torch.from_numpy(x0_b).to(self.dev))
+        KS = (K, self.row)
+        self.X = torch.empty(KS, dtype=f, device=self.dev)
+        self.M = torch.empty(KS, dtype=f, device=self.dev)
+        self.V = torch.empty(KS, dtype=f, device=self.dev) if inner == "adamw" else None
+        self.G = torch.zeros(KS, dtype=f if grad_dtype == "f32" else torch.bfloat16, device=self.dev)
+        self.XG = torch.empty(self.row, dtype=f, device=self.dev)
+        self.OM = torch.empty(self.row, dtype=f, device=self.dev)
+        self.lib = Palsgd(self.cfg, self.X, self.M, self.V, self.G, self.XG, self.OM, self.row, x0=x0)
+        torch.cuda.synchronize()
+        del x0
+        self.ora = oracle.OracleState(K, x0_b, [0], [B], inner=inner, grad_dtype=grad_dtype, p=p, H=H, seed=seed, **hyper)
+        self.t = 0
+
+    def tile_into(self, dst_row, block):
+        """dst_row[i] = block[i mod B] over the padded row, zero on the padding between tensors."""
+        n = self.reps * self.B
+        if self.reps:
+            dst_row[:n].view(self.reps, self.B).copy_(block.unsqueeze(0).expand(self.reps, self.B))
+        if self.tail:
+            dst_row[n:self.row].copy_(block[:self.tail])
+        if self.pad_idx.numel():
+            dst_row.index_fill_(0, self.pad_idx, 0)
+
+    def make_gradients(self):
+        g = (self.ora.X - self.c_b[None, :]) + np.float32(self.sigma) * self.rng.standard_normal(
+            self.ora.X.shape, dtype=np.float32)
+        g = g.astype(np.float32)
+        if self.grad_dtype == "f32":
+            self.ora.G[...] = g
+            gd = torch.from_numpy(g).to(self.dev)
+        else:
+            bits = to_bf16_bits(g)
+            self.ora.G[...] = bits
+            gd = torch.from_numpy(bits.view(np.int16)).to(self.dev).view(torch.bfloat16)
+        for k in range(self.K):
+            self.tile_into(self.G[k], gd[k])
+
+    def iterate(self, steps, *, fused_sync=False):
+        for _ in range(steps):
+            t = self.t
+            self.make_gradients()
+            mask_o, synced = self.ora.iteration(t, self.alpha, self.eta)
+            assert np.array_equal(self.lib.palsgd_draw(t), mask_o), f"draws differ at t={t}"
+            assert synced == ((t + 1) % self.H == 0)
+            if synced and fused_sync:
+                self.lib.palsgd_step_sync(t, self.alpha, self.eta)
+            else:
+                self.lib.palsgd_step(t, self.alpha, self.eta)
+                if synced:
+                    self.lib.palsgd_outer_step(t)
+            self.t += 1
+        torch.cuda.synchronize()
+
+    def compare(self, rtol=RTOL, atol=ATOL, chunk=1 << 26):
+        """Every element of every state array against the oracle's value for its position mod B."""
+        tau, n_outer = self.lib.palsgd_get_state()
+        assert tau == [int(v) for v in self.ora.tau] and n_outer == self.ora.n_outer
+        rows = [("XG", self.XG, self.ora.XG), ("OM", self.OM, self.ora.OM)]
+        for k in range(self.K):
+            rows += [(f"X[{k}]", self.X[k], self.ora.X[k]), (f"M[{k}]", self.M[k], self.ora.M[k])]
+            if self.V is not None:
+                rows.append((f"V[{k}]", self.V[k], self.ora.V[k]))
+        want_row = torch.empty(self.row, dtype=torch.float32, device=self.dev)
+        worst, checked = 0.0, 0
+        for name, got, want in rows:
+            self.tile_into(want_row, torch.from_numpy(np.ascontiguousarray(want)).to(self.dev))
+            for a in range(0, self.row, chunk):
+                w = want_row[a:a + chunk].double()
+                gdev = got[a:a + chunk]
+                assert bool(torch.isfinite(gdev).all()), name
+                ratio = (gdev.double() - w).abs() / (rtol * w.abs() + atol)
+                r = float(ratio.max())
+                assert r <= 1.0, f"{name}: {int((ratio > 1).sum())} elements outside tolerance in [{a}, {a + chunk}), worst {r:.3g}"
+                worst = max(worst, r)
+                checked += gdev.numel()
+            if self.pad_idx.numel():
+                assert not bool(got.index_select(0, self.pad_idx).any()), f"{name}: padding became non-zero"
+        return worst, checked
+
+    def close(self):
+        self.lib.palsgd_destroy()

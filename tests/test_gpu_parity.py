@@ -182,6 +182,35 @@ def test_config_gptneo1p3b_k8_sampled():
     _sampled("gptneo1p3b_k8", steps=128, per_edge=256, n_random=1 << 16)
 
 
+def _every_element(name, steps=None, fused_sync=False, B=1 << 16):
+    """Full-size buffers, the benchmark's launch configuration, inputs periodic along the row: all elements of
+    all state arrays are compared with the oracle (which runs one period), after all steps."""
+    from parity import PeriodicRun
+    w = workload(name)
+    r = PeriodicRun(w.K, w.numels, B=B, inner=w.inner, grad_dtype=w.grad_dtype, p=w.p, H=w.H, alpha=w.alpha, eta=w.eta,
+                    sigma=w.sigma, seed=w.seed, weight_decay=w.weight_decay, momentum=w.momentum, outer_lr=w.outer_lr,
+                    outer_momentum=w.outer_momentum)
+    r.iterate(steps or w.steps, fused_sync=fused_sync)
+    worst, checked = r.compare()
+    n_arrays = 3 if w.inner == "adamw" else 2
+    assert checked == (n_arrays * w.K + 2) * r.row
+    print(f"{name}: {checked} elements checked, worst err/bound {worst:.3g}")
+    r.close()
+
+
+@pytest.mark.parametrize("name,fused_sync", [("gptneo125m_k8", False), ("gptneo125m_k8", True), ("resnet50_k8", False),
+                                             ("gptneo125m_k16", False), ("smallcnn_k64", True)])
+def test_config_every_element(name, fused_sync):
+    _every_element(name, fused_sync=fused_sync)
+
+
+def test_config_gptneo1p3b_k8_every_element():
+    free, total = torch.cuda.mem_get_info()
+    if free < 200 * 2 ** 30:
+        pytest.skip("needs about 200 GB of free device memory")
+    _every_element("gptneo1p3b_k8", steps=128)
+
+
 def test_deterministic_and_stream_independent():
     """Same inputs give bit-identical results run to run, on the default stream and on two contexts that
     work concurrently on two side streams (fixed summation orders, no atomics)."""
