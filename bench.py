@@ -232,6 +232,9 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
         ddp_b = K * gB + state + 4 + 4 * K + (state - 4)  # read K gradients + x, m(, v); write XG, K rows of x, one of m(, v)
         ms = timed(lambda: ctx.palsgd_ddp_step(0, w.alpha, None, stream))
         res["ddp_step"] = dict(ms=ms, gbps=float(P) * ddp_b / ms / 1e6, bytes_per_elem=ddp_b)
+        ddp_s = ddp_b - 4 * K                            # the model kept once (XG): no row stores
+        ms = timed(lambda: ctx.palsgd_ddp_step_shared(0, w.alpha, None, stream))
+        res["ddp_step_shared"] = dict(ms=ms, gbps=float(P) * ddp_s / ms / 1e6, bytes_per_elem=ddp_s)
     ctx.palsgd_destroy()
     return res
 
@@ -333,7 +336,7 @@ def main():
     if a.graph:
         out["hip_graph_replay"] = r["graph"]
     if a.extra_kernels:
-        out["extra_kernels"] = {k: r[k] for k in ("gradient_branch_only", "mixing_branch_only", "ddp_step",
+        out["extra_kernels"] = {k: r[k] for k in ("gradient_branch_only", "mixing_branch_only", "ddp_step", "ddp_step_shared",
                                                   "clip_grad_norm", "clip_mean_grad_norm", "diagnostics") if k in r}
     print(json.dumps(out))
 

@@ -161,16 +161,31 @@ palsgd_status palsgd_outer_step_diag(palsgd_ctx *ctx, uint64_t t, float *diag_ou
  * rescale: there is no mixing branch);  the result is stored to XG and to every row of X,
  * and every worker's step count advances.  The InnerOPT state of the identical workers
  * is kept once, in worker 0's rows of M, V; rows 1..K-1 are stale during the warm-up and
- * are filled from row 0 by the first palsgd_inner_step / palsgd_step /
- * palsgd_capturable_begin that follows, or by palsgd_ddp_finish.
+ * are filled from row 0 by the first palsgd_inner_step / palsgd_pseudo_sync / palsgd_step /
+ * palsgd_step_sync / palsgd_outer_step / palsgd_diagnostics / palsgd_capturable_begin that
+ * follows, or by palsgd_ddp_finish.
  * Precondition: all workers are identical (true from palsgd_init through the warm-up);
  * the common model is read from XG, the common InnerOPT state from worker 0.  ESTATE if
  * the workers' step counts differ.  OM is not touched.  The per-worker clipping scales of
  * palsgd_clip_grad_norm are not consumed here; the scale of palsgd_clip_mean_grad_norm is. */
 palsgd_status palsgd_ddp_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, const float *grad_scale, void *stream);
 
+/* The same DDP step with the model kept once as well (Sec. 3.1: in DDP every worker holds
+ * the same model): the new model is stored to XG only, which saves the K row stores of
+ * palsgd_ddp_step (4K of 4K + 24 + K*sizeof(g) bytes per element with AdamW).  During such
+ * a warm-up the workers' model IS XG: the caller computes every worker's gradient at XG,
+ * and the K rows of X are stale.  They are filled from XG, together with the InnerOPT
+ * state, by palsgd_ddp_finish or by the first later call of this context that reads or
+ * updates them (palsgd_inner_step, palsgd_pseudo_sync, palsgd_step, palsgd_step_sync,
+ * palsgd_outer_step, palsgd_outer_step_diag, palsgd_diagnostics, palsgd_capturable_begin);
+ * a palsgd_ddp_step stores all rows itself.  Arguments, preconditions and errors as
+ * palsgd_ddp_step. */
+palsgd_status palsgd_ddp_step_shared(palsgd_ctx *ctx, uint64_t t, float alpha_t, const float *grad_scale,
+                                     void *stream);
+
 /* End of the warm-up made explicit: copies worker 0's InnerOPT state into rows 1..K-1 of
- * M, V if DDP steps left them stale; no launch otherwise. */
+ * M, V, and XG into the K rows of X, where DDP steps left them stale (one launch); no
+ * launch otherwise. */
 palsgd_status palsgd_ddp_finish(palsgd_ctx *ctx, void *stream);
 
 /* Gradient clipping by the global L2 norm of each worker's gradient (App. B says the GPT-Neo runs
@@ -218,7 +233,8 @@ palsgd_status palsgd_diagnostics(palsgd_ctx *ctx, float *out_dev, void *stream);
  * palsgd_capturable_end: waits for `stream`, reads t and the step counts back (t_out may be
  *   NULL) and returns the context to host-driven calls.
  * While the schedule is device-resident, palsgd_inner_step, palsgd_pseudo_sync, palsgd_step,
- * palsgd_step_sync, palsgd_ddp_step, palsgd_get_state and palsgd_set_state return ESTATE. */
+ * palsgd_step_sync, palsgd_ddp_step, palsgd_ddp_step_shared, palsgd_get_state and
+ * palsgd_set_state return ESTATE. */
 palsgd_status palsgd_capturable_begin(palsgd_ctx *ctx, uint64_t t0, void *stream);
 palsgd_status palsgd_step_capturable(palsgd_ctx *ctx, const float *alpha_eta_dev, void *stream);
 palsgd_status palsgd_capturable_end(palsgd_ctx *ctx, uint64_t *t_out, void *stream);

@@ -26,7 +26,8 @@ EXPORTS = ("palsgd_layout", "palsgd_init", "palsgd_draw", "palsgd_inner_step", "
            "palsgd_step", "palsgd_outer_step", "palsgd_get_state", "palsgd_set_state",
            "palsgd_last_error", "palsgd_destroy", "palsgd_set_tuning", "palsgd_ddp_step",
            "palsgd_clip_grad_norm", "palsgd_diagnostics", "palsgd_outer_step_diag", "palsgd_capturable_begin",
-           "palsgd_step_capturable", "palsgd_capturable_end", "palsgd_ddp_finish", "palsgd_clip_mean_grad_norm", "palsgd_step_sync")
+           "palsgd_step_capturable", "palsgd_capturable_end", "palsgd_ddp_finish", "palsgd_clip_mean_grad_norm", "palsgd_step_sync",
+           "palsgd_ddp_step_shared")
 
 
 class PalsgdError(RuntimeError):
@@ -81,6 +82,8 @@ def lib() -> C.CDLL:
         L.palsgd_outer_step.argtypes = [vp, u64, vp]
         L.palsgd_ddp_step.restype = st
         L.palsgd_ddp_step.argtypes = [vp, u64, f, C.POINTER(f), vp]
+        L.palsgd_ddp_step_shared.restype = st
+        L.palsgd_ddp_step_shared.argtypes = [vp, u64, f, C.POINTER(f), vp]
         L.palsgd_ddp_finish.restype = st
         L.palsgd_ddp_finish.argtypes = [vp, vp]
         L.palsgd_clip_grad_norm.restype = st
@@ -223,6 +226,10 @@ class Palsgd:
     def palsgd_ddp_step(self, t, alpha_t, grad_scale=None, stream=None):
         gs, gsp = _f32(grad_scale)
         _check(lib().palsgd_ddp_step(self._ctx, int(t), alpha_t, gsp, _stream_handle(stream)), self._ctx)
+
+    def palsgd_ddp_step_shared(self, t, alpha_t, grad_scale=None, stream=None):
+        gs, gsp = _f32(grad_scale)
+        _check(lib().palsgd_ddp_step_shared(self._ctx, int(t), alpha_t, gsp, _stream_handle(stream)), self._ctx)
 
     def palsgd_ddp_finish(self, stream=None):
         _check(lib().palsgd_ddp_finish(self._ctx, _stream_handle(stream)), self._ctx)

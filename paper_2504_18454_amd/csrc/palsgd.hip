@@ -471,8 +471,9 @@ __global__ void schedule_set_kernel(DevSchedule* __restrict__ s, uint64_t t0, Ta
 // DDP step of the warm-up phase (Sec. 3.1: All-Reduce of the gradient, then the optimizer
 // update, identical on every worker; Sec. 4.3).  One wavefront per tile: weighted mean of the
 // K gradient rows (k ascending, eight loads in flight), InnerOPT on the common model (read
-// from XG) with the common state (replica 0's), model stored to XG and all K rows of X, state
-// to replica 0 only: the other replicas' copies are made once, when the warm-up ends.
+// from XG) with the common state (replica 0's), model stored to XG and to the first x_rows
+// rows of X (K, or 0 when the rows are left to the end of the warm-up), state to replica 0
+// only: the other replicas' copies are made once, when the warm-up ends.
 struct DdpArgs {
     float w[PALSGD_MAX_K];  // grad_scale[k]
     float inv_k, lr, c1, c2;
@@ -484,7 +485,7 @@ __global__ __launch_bounds__(kWave) void ddp_kernel(const DdpArgs a, const float
                                                     float* __restrict__ V, const void* __restrict__ G,
                                                     float* __restrict__ XG,
                                                     const float* __restrict__ clip_scale, uint64_t n,
-                                                    uint64_t row_stride, uint32_t K, Hyper h) {
+                                                    uint64_t row_stride, uint32_t K, uint32_t x_rows, Hyper h) {
     const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
     if (e >= n) return;
     typedef GradLoad<GDT> GL;
@@ -510,21 +511,29 @@ __global__ __launch_bounds__(kWave) void ddp_kernel(const DdpArgs a, const float
     st4(XG + e, xv);
     st4(M + e, mv);  // the common InnerOPT state lives in replica 0 during the warm-up
     if (INNER == PALSGD_INNER_ADAMW) st4(V + e, vv);
-    for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xv);
+    for (uint32_t k = 0; k < x_rows; ++k) st4(X + (uint64_t)k * row_stride + e, xv);
 }
 
-// End of the warm-up: replicas 1..K-1 take over the common InnerOPT state of replica 0.
-__global__ __launch_bounds__(kWave) void moments_broadcast_kernel(float* __restrict__ M, float* __restrict__ V,
-                                                                  uint64_t n, uint64_t row_stride, uint32_t K) {
+// End of the warm-up: replicas 1..K-1 take over the common InnerOPT state of replica 0
+// (M, and V unless NULL), and all K rows of X take the common model from XG (unless X is
+// NULL: the DDP steps kept the rows current themselves).
+__global__ __launch_bounds__(kWave) void warmup_broadcast_kernel(float* __restrict__ M, float* __restrict__ V,
+                                                                 float* __restrict__ X, const float* __restrict__ XG,
+                                                                 uint64_t n, uint64_t row_stride, uint32_t K) {
     const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
     if (e >= n) return;
-    const f4 mv = ld4(M + e);
-    f4 vv;
+    f4 mv, vv, xv;
+    if (M) mv = ld4(M + e);
     if (V) vv = ld4(V + e);
+    if (X) {
+        xv = ld4(XG + e);
+        st4(X + e, xv);
+    }
     for (uint32_t k = 1; k < K; ++k) {
         const uint64_t o = (uint64_t)k * row_stride + e;
-        st4(M + o, mv);
+        if (M) st4(M + o, mv);
         if (V) st4(V + o, vv);
+        if (X) st4(X + o, xv);
     }
 }
 
@@ -721,6 +730,7 @@ struct palsgd_ctx {
     bool clip_armed = false;       // d_scratch holds clipping scales for the next gradient step
     bool clip_mean_armed = false;  // ... and the scale of the averaged gradient for the next DDP step
     bool moments_shared = false;   // after DDP steps: only replica 0's M, V are current
+    bool model_shared = false;     // after palsgd_ddp_step_shared: the rows of X are stale, the model is XG
     void* d_schedule = nullptr;    // DevSchedule of the graph-capturable mode
     bool capturable = false;       // between palsgd_capturable_begin and palsgd_capturable_end
     uint32_t step_waves = 0;       // cap on resident wavefronts per CU, 0 = derive from bytes per wavefront
@@ -882,18 +892,24 @@ void launch_step(palsgd_ctx* c, const StepArgs& args, const Slot* dev_slots, uin
 #undef PALSGD_STEP
 }
 
-// Replicas 1..K-1 get replica 0's InnerOPT state if DDP steps left it shared.
-palsgd_status unshare_moments(palsgd_ctx* c, const char* who, hipStream_t st) {
-    if (!c->moments_shared) return PALSGD_OK;
-    if (c->cfg.K > 1) {
-        const uint32_t bytes = (c->cfg.inner == PALSGD_INNER_ADAMW ? 8u : 4u) * c->cfg.K * kTile;
-        float* v = c->cfg.inner == PALSGD_INNER_ADAMW ? c->buf.V : nullptr;
-        moments_broadcast_kernel<<<tile_count(c), kWave, lds_cap(auto_waves(bytes, 4), 0), st>>>(
-            c->buf.M, v, c->P_padded, c->buf.row_stride, c->cfg.K);
+// What the DDP steps of the warm-up kept once for the identical workers goes to every worker:
+// replica 0's InnerOPT state to replicas 1..K-1, the common model XG to the K rows of X.
+palsgd_status end_warmup_sharing(palsgd_ctx* c, const char* who, hipStream_t st) {
+    if (!c->moments_shared && !c->model_shared) return PALSGD_OK;
+    const uint32_t K = c->cfg.K;
+    const bool adamw = c->cfg.inner == PALSGD_INNER_ADAMW;
+    float* m = c->moments_shared && K > 1 ? c->buf.M : nullptr;
+    float* v = m && adamw ? c->buf.V : nullptr;
+    float* x = c->model_shared ? c->buf.X : nullptr;
+    if (m || x) {
+        const uint32_t bytes = ((m ? (adamw ? 8u : 4u) : 0u) + (x ? 4u : 0u)) * K * kTile;
+        warmup_broadcast_kernel<<<tile_count(c), kWave, lds_cap(auto_waves(bytes, 4), 0), st>>>(
+            m, v, x, c->buf.XG, c->P_padded, c->buf.row_stride, K);
         palsgd_status rc = check_launch(c, who);
         if (rc != PALSGD_OK) return rc;
     }
     c->moments_shared = false;
+    c->model_shared = false;
     return PALSGD_OK;
 }
 
@@ -967,11 +983,6 @@ palsgd_status plan_slots(palsgd_ctx* c, const char* who, uint64_t t, float alpha
     return PALSGD_OK;
 }
 
-// What a launch with gradient steps needs beforehand: every replica's own InnerOPT state.
-palsgd_status prepare_gradient_launch(palsgd_ctx* c, const char* who, hipStream_t st) {
-    return unshare_moments(c, who, st);
-}
-
 // Shared body of palsgd_inner_step / palsgd_pseudo_sync / palsgd_step.
 palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alpha, float eta,
                            const float* grad_scale, const uint8_t* mask_override, bool do_grad, bool do_mix,
@@ -986,10 +997,8 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
     bool any_grad = false;
     for (uint32_t k = 0; k < K; ++k) any_grad = any_grad || stepped[k];
     hipStream_t st = (hipStream_t)stream;
-    if (any_grad) {
-        rc = prepare_gradient_launch(c, who, st);
-        if (rc != PALSGD_OK) return rc;
-    }
+    rc = end_warmup_sharing(c, who, st);  // every worker needs its own model row and InnerOPT state from here on
+    if (rc != PALSGD_OK) return rc;
     // clipping scales computed by palsgd_clip_grad_norm are consumed by the first gradient step after it
     const float* clip = any_grad && c->clip_armed ? clip_scales(c) : nullptr;
     dispatch_step(c, args, nullptr, n, any_grad, clip, st);
@@ -1158,10 +1167,8 @@ palsgd_status palsgd_step_sync(palsgd_ctx* ctx, uint64_t t, float alpha_t, float
     bool any_grad = false;
     for (uint32_t k = 0; k < K; ++k) any_grad = any_grad || stepped[k];
     hipStream_t st = (hipStream_t)stream;
-    if (any_grad) {
-        rc = prepare_gradient_launch(ctx, "palsgd_step_sync", st);
-        if (rc != PALSGD_OK) return rc;
-    }
+    rc = end_warmup_sharing(ctx, "palsgd_step_sync", st);
+    if (rc != PALSGD_OK) return rc;
     const float* clip = any_grad && ctx->clip_armed ? clip_scales(ctx) : nullptr;
     OuterArgs a{(float)(1.0 / (double)K), ctx->cfg.outer_lr, ctx->cfg.outer_momentum, ctx->cfg.outer_nesterov ? 1 : 0};
     const bool adamw = ctx->cfg.inner == PALSGD_INNER_ADAMW, bf16 = ctx->cfg.grad_dtype == PALSGD_GRAD_BF16;
@@ -1192,6 +1199,10 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
     const uint32_t waves = ctx->outer_waves ? ctx->outer_waves
                                             : auto_waves((8u * K + 16u) * kTile, 4);  // rows go 8 at a time: 4 is best from K=16 up
     const palsgd_buffers& b = ctx->buf;
+    {
+        palsgd_status rc = end_warmup_sharing(ctx, who, st);  // the rows of X are read here
+        if (rc != PALSGD_OK) return rc;
+    }
     if (diag_out_dev) {
         palsgd_status rc = ensure_scratch(ctx);
         if (rc != PALSGD_OK) return rc;
@@ -1228,26 +1239,26 @@ palsgd_status palsgd_outer_step_diag(palsgd_ctx* ctx, uint64_t t, float* diag_ou
     return outer_impl(ctx, "palsgd_outer_step_diag", t, diag_out_dev, stream);
 }
 
-palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const float* grad_scale, void* stream) {
-    (void)t;
+static palsgd_status ddp_impl(palsgd_ctx* ctx, const char* who, float alpha_t, const float* grad_scale, bool share_model,
+                              void* stream) {
     if (!ctx) {
-        set_error(g_error, "palsgd_ddp_step: NULL context");
+        set_error(g_error, "%s: NULL context", who);
         return PALSGD_EINVAL;
     }
     if (!(alpha_t >= 0.0f) || !std::isfinite(alpha_t)) {
-        set_error(ctx->error, "palsgd_ddp_step: alpha_t must be finite and >= 0");
+        set_error(ctx->error, "%s: alpha_t must be finite and >= 0", who);
         return PALSGD_EINVAL;
     }
     if (ctx->capturable) {
-        set_error(ctx->error, "palsgd_ddp_step: not available while the schedule is device-resident");
+        set_error(ctx->error, "%s: not available while the schedule is device-resident", who);
         return PALSGD_ESTATE;
     }
     const uint32_t K = ctx->cfg.K;
     for (uint32_t k = 1; k < K; ++k)
         if (ctx->tau[k] != ctx->tau[0]) {
-            set_error(ctx->error, "palsgd_ddp_step: workers have taken different numbers of gradient steps "
+            set_error(ctx->error, "%s: workers have taken different numbers of gradient steps "
                                   "(%llu vs %llu): the DDP step needs identical workers",
-                      (unsigned long long)ctx->tau[0], (unsigned long long)ctx->tau[k]);
+                      who, (unsigned long long)ctx->tau[0], (unsigned long long)ctx->tau[k]);
             return PALSGD_ESTATE;
         }
     DdpArgs a;
@@ -1255,7 +1266,7 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
     if (grad_scale)
         for (uint32_t k = 0; k < K; ++k) {
             if (!std::isfinite(grad_scale[k])) {
-                set_error(ctx->error, "palsgd_ddp_step: grad_scale[%u] is not finite", k);
+                set_error(ctx->error, "%s: grad_scale[%u] is not finite", who, k);
                 return PALSGD_EINVAL;
             }
             a.w[k] = grad_scale[k];
@@ -1271,7 +1282,9 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
     }
     const uint64_t n = ctx->P_padded;
     const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
-    const uint32_t per_elem = (adamw ? 24u : 16u) + 4u * K + K * (bf16 ? 2u : 4u);
+    // rows of X this launch stores: all K, or none when the model stays shared (it is then XG alone)
+    const uint32_t x_rows = share_model ? 0u : K;
+    const uint32_t per_elem = (adamw ? 24u : 16u) + 4u * x_rows + K * (bf16 ? 2u : 4u);
     const uint32_t lds = lds_cap(ctx->outer_waves ? ctx->outer_waves : auto_waves(per_elem * kTile, 4), 0);
     Hyper h = hyper_of(ctx);
     hipStream_t st = (hipStream_t)stream;
@@ -1279,20 +1292,31 @@ palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const 
     const float* clip = ctx->clip_mean_armed ? mean_clip_scale(ctx) : nullptr;
 #define PALSGD_DDP(I, D)                                                                                           \
     if (ctx->wd_uniform)                                                                                           \
-        ddp_kernel<I, D, false><<<tiles, kWave, lds, st>>>(a, nullptr, b.X, b.M, b.V, b.G, b.XG, clip, n, b.row_stride, K, h); \
+        ddp_kernel<I, D, false><<<tiles, kWave, lds, st>>>(a, nullptr, b.X, b.M, b.V, b.G, b.XG, clip, n, b.row_stride, K, x_rows, h); \
     else                                                                                                           \
-        ddp_kernel<I, D, true><<<tiles, kWave, lds, st>>>(a, ctx->d_wd_tab, b.X, b.M, b.V, b.G, b.XG, clip, n, b.row_stride, K, h);
+        ddp_kernel<I, D, true><<<tiles, kWave, lds, st>>>(a, ctx->d_wd_tab, b.X, b.M, b.V, b.G, b.XG, clip, n, b.row_stride, K, x_rows, h);
     if (adamw && bf16) { PALSGD_DDP(PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16) }
     else if (adamw) { PALSGD_DDP(PALSGD_INNER_ADAMW, PALSGD_GRAD_F32) }
     else if (bf16) { PALSGD_DDP(PALSGD_INNER_SGDM, PALSGD_GRAD_BF16) }
     else { PALSGD_DDP(PALSGD_INNER_SGDM, PALSGD_GRAD_F32) }
 #undef PALSGD_DDP
-    palsgd_status rc = check_launch(ctx, "palsgd_ddp_step");
+    palsgd_status rc = check_launch(ctx, who);
     if (rc != PALSGD_OK) return rc;
     for (uint32_t k = 0; k < K; ++k) ctx->tau[k] += 1;
     ctx->moments_shared = true;
+    ctx->model_shared = share_model;  // a step that stores all K rows also ends an earlier sharing of the model
     ctx->clip_mean_armed = false;
     return PALSGD_OK;
+}
+
+palsgd_status palsgd_ddp_step(palsgd_ctx* ctx, uint64_t t, float alpha_t, const float* grad_scale, void* stream) {
+    (void)t;
+    return ddp_impl(ctx, "palsgd_ddp_step", alpha_t, grad_scale, false, stream);
+}
+
+palsgd_status palsgd_ddp_step_shared(palsgd_ctx* ctx, uint64_t t, float alpha_t, const float* grad_scale, void* stream) {
+    (void)t;
+    return ddp_impl(ctx, "palsgd_ddp_step_shared", alpha_t, grad_scale, true, stream);
 }
 
 palsgd_status palsgd_ddp_finish(palsgd_ctx* ctx, void* stream) {
@@ -1300,7 +1324,7 @@ palsgd_status palsgd_ddp_finish(palsgd_ctx* ctx, void* stream) {
         set_error(g_error, "palsgd_ddp_finish: NULL context");
         return PALSGD_EINVAL;
     }
-    return unshare_moments(ctx, "palsgd_ddp_finish", (hipStream_t)stream);
+    return end_warmup_sharing(ctx, "palsgd_ddp_finish", (hipStream_t)stream);
 }
 
 palsgd_status palsgd_clip_grad_norm(palsgd_ctx* ctx, float max_norm, float* norms_out_dev, void* stream) {
@@ -1386,6 +1410,8 @@ palsgd_status palsgd_diagnostics(palsgd_ctx* ctx, float* out_dev, void* stream) 
     const uint32_t K = ctx->cfg.K, n_part = diag_parts(ctx);
     const float inv_k = (float)(1.0 / (double)K);
     hipStream_t st = (hipStream_t)stream;
+    rc = end_warmup_sharing(ctx, "palsgd_diagnostics", st);  // the rows of X are read here
+    if (rc != PALSGD_OK) return rc;
     diag_kernel<<<n_part, kWave, 0, st>>>(ctx->buf.X, ctx->buf.XG, scratch_partials(ctx), ctx->P_padded,
                                           ctx->buf.row_stride, K, inv_k, n_part);
     fold_kernel<<<dim3(kFold, 2), kThreads, 0, st>>>(scratch_partials(ctx), n_part, scratch_fold(ctx));
@@ -1408,7 +1434,7 @@ palsgd_status palsgd_capturable_begin(palsgd_ctx* ctx, uint64_t t0, void* stream
     }
     (void)lds_per_cu();
     {
-        palsgd_status rc = unshare_moments(ctx, "palsgd_capturable_begin", (hipStream_t)stream);
+        palsgd_status rc = end_warmup_sharing(ctx, "palsgd_capturable_begin", (hipStream_t)stream);
         if (rc != PALSGD_OK) return rc;
     }
     TauArgs a;

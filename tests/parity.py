@@ -188,9 +188,10 @@ class Run:
                 self.compare()
         torch.cuda.synchronize()
 
-    def ddp_iterate(self, steps, grad_scale=None, clip=None):
+    def ddp_iterate(self, steps, grad_scale=None, clip=None, shared=False):
         """DDP warm-up steps: every worker applies the update of the averaged gradient (clipped by the
-        norm of that average when `clip` is given; a whole-row reduction, so full-coverage runs only)."""
+        norm of that average when `clip` is given; a whole-row reduction, so full-coverage runs only).
+        shared: through palsgd_ddp_step_shared, which leaves the rows of X to the end of the warm-up."""
         gs64 = None if grad_scale is None else np.asarray(grad_scale, np.float32).astype(np.float64)
         for _ in range(steps):
             self.make_gradients()
@@ -205,7 +206,7 @@ class Run:
                 gs_o = (np.ones(self.K) if gs64 is None else gs64) * scale
                 self.last_scales = np.array([scale])
             self.ora.ddp_step(self.alpha, grad_scale=gs_o)
-            self.lib.palsgd_ddp_step(self.t, self.alpha, grad_scale)
+            (self.lib.palsgd_ddp_step_shared if shared else self.lib.palsgd_ddp_step)(self.t, self.alpha, grad_scale)
             self.t += 1
         torch.cuda.synchronize()
 

@@ -41,6 +41,61 @@ def test_ddp_warmup_then_palsgd(inner, grad_dtype, K):
     r.close()
 
 
+@pytest.mark.parametrize("ender", ["finish", "step", "mix_only", "sync_step", "outer", "outer_diag", "diagnostics",
+                                   "capturable", "ddp_step"])
+@pytest.mark.parametrize("inner,grad_dtype,K", [("adamw", "bf16", 8), ("sgdm", "f32", 3)])
+def test_ddp_shared_model_warmup(inner, grad_dtype, K, ender):
+    """Warm-up through palsgd_ddp_step_shared (the model lives in XG alone): whichever call comes next
+    must first give every worker its model row and InnerOPT state."""
+    r = _run(K=K, numels=RAGGED, inner=inner, grad_dtype=grad_dtype, p=0.25, H=3, seed=50 + K, sigma=0.05,
+             wd_mult=[1, 0, 1, 1, 0.5, 1, 0], row_extra=1)
+    r.X[:, :r.row] = 123.0                                   # rows of X are not read during such a warm-up
+    r.ddp_iterate(5 if ender == "sync_step" else 4, shared=True)   # H = 3: t = 5 is a synchronisation step
+    torch.cuda.synchronize()
+    assert bool((r.X[:, :r.row] == 123.0).all())             # ... and not written either
+    if ender == "finish":
+        r.lib.palsgd_ddp_finish()
+        r.compare()
+        for k in range(K):
+            assert torch.equal(r.X[k], r.XG) and torch.equal(r.M[k], r.M[0])
+        r.lib.palsgd_ddp_finish()                            # nothing left to do
+    elif ender == "step":
+        r.iterate(1)
+    elif ender == "mix_only":
+        r.iterate(1, mask_fn=lambda t: [1] * K)
+    elif ender == "sync_step":
+        r.iterate(1, fused_sync=True)
+    elif ender == "outer":                                   # an outer step on identical workers: Delta = 0
+        r.ora.outer_step()
+        r.lib.palsgd_outer_step(r.t)
+    elif ender == "outer_diag":
+        out = torch.empty(2, dtype=torch.float32, device="cuda:0")
+        r.ora.outer_step()
+        r.lib.palsgd_outer_step_diag(r.t, out)
+        assert out.cpu().tolist() == [0.0, 0.0]
+    elif ender == "diagnostics":
+        out = torch.empty(2, dtype=torch.float32, device="cuda:0")
+        r.lib.palsgd_diagnostics(out)
+        assert out.cpu().tolist() == [0.0, 0.0]
+    elif ender == "capturable":
+        ae = torch.tensor([r.alpha, r.eta], dtype=torch.float32, device="cuda:0")
+        r.lib.palsgd_capturable_begin(r.t)
+        r.make_gradients()
+        r.ora.iteration(r.t, r.alpha, r.eta)
+        r.lib.palsgd_step_capturable(ae)
+        r.t += 1
+        assert r.lib.palsgd_capturable_end() == r.t
+    elif ender == "ddp_step":
+        r.ddp_iterate(1, shared=False)                       # stores all rows itself (InnerOPT state still shared)
+        for k in range(K):
+            assert torch.equal(r.X[k], r.XG)
+    if ender != "ddp_step":
+        r.compare()
+    r.iterate(4)
+    r.compare()
+    r.close()
+
+
 def test_ddp_then_device_schedule():
     r = _run(K=4, numels=RAGGED, grad_dtype="bf16", p=0.25, H=3, seed=36, sigma=0.05)
     r.ddp_iterate(4)

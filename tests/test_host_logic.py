@@ -162,7 +162,7 @@ def test_binding_structs_match_the_header_layout(tmp_path):
 
 def test_plain_c_program_is_built_and_fails_cleanly_without_a_gpu():
     """tests/c_abi_parity links against the library and the HIP runtime; without a device it stops at its
-    first allocation with an error message (on a GPU machine it runs to completion, see the GPU tests)."""
+    first allocation with an error message (with a GPU it runs to completion, see the GPU tests)."""
     import subprocess
     exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi_parity")
     if not os.path.exists(exe):
