@@ -166,6 +166,7 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     fused_ms = [all_ms[i] for i in range(steps) if fused_sync and synced[i]]
     res = dict(
         elapsed=elapsed, updates=float(K) * P * steps, row=row,
+        step_kernel_ms_spread=[float(np.percentile(step_ms, q)) for q in (0, 10, 50, 90, 100)],
         step_kernel_ms=float(np.mean(step_ms)), step_kernel_gbps=sum(step_bytes) / (sum(step_ms) * 1e-3) / 1e9,
         step_kernel_bytes=float(np.mean(step_bytes)),
         outer_kernel_ms=float(np.mean(outer_ms)) if outer_ms else None,
@@ -322,6 +323,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": r["step_kernel_gbps"],
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": r["step_kernel_gbps"] / HBM_PEAK_GBPS,
                      "traffic": measured_traffic(a.workload), "bytes_per_launch": r["step_kernel_bytes"], "ms_per_launch": r["step_kernel_ms"],
+                     "ms_per_launch_min_p10_p50_p90_max": r["step_kernel_ms_spread"],
                      "bytes_per_elem": {"grad": gb, "mix": 12}},
         "outer_kernel": {"ms_per_launch": r["outer_kernel_ms"], "achieved": r["outer_kernel_gbps"], "unit": "GB/s",
                          "frac": (r["outer_kernel_gbps"] / HBM_PEAK_GBPS) if r["outer_kernel_gbps"] else None,
