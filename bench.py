@@ -33,23 +33,24 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of step_kernel from two rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE, each scaled by
 # what it reads for the 1 GiB set-up copy); summary in profiles/gptneo125m_k8_hbm_counters.txt.  The figure
 # holds for one kernel source only: it is reported as null as soon as the code of step_kernel and its helpers
-# in csrc/palsgd.hip (comments and white space aside) differs from the file the counters were taken with.
+# (csrc/device_common.h and csrc/step_kernel.h, comments and white space aside) differs from the files the
+# counters were taken with.
 TRAFFIC = {
     "workload": "gptneo125m_k8",
-    "kernel_source_sha256": "55c71347912517f622b46ada00ea550c483ed8d3c2363707ba4991725f6c9363",
-    "bytes_per_launch": 25224123403.4,            # mean over the 16 launches t = 0..15 of the counter runs
+    "kernel_source_sha256": "2b4b472afa213a9d7fc1d8fd969690649f8cde613eeda7b322a7d303d24f09fa",
+    "bytes_per_launch": 25224105547.8,            # mean over the 16 launches t = 0..15 of the counter runs
     "algorithmic_bytes_same_launches": 25224565440.0,
 }
 
 
-def kernel_source_digest(path=None):
-    """SHA-256 of the code of step_kernel and its helpers (everything above the marker that follows the
-    kernel in the source) with comments and white space removed: a change of that kernel's code changes it, a
-    change of wording, of other kernels or of host code does not."""
+def kernel_source_digest(csrc=None):
+    """SHA-256 of the code of step_kernel and its helpers (the two headers that hold them) with comments and
+    white space removed: a change of that kernel's code changes it, a change of wording, of other kernels or
+    of host code does not."""
     import hashlib
     import re
-    path = path or os.path.join(ROOT, "paper_2504_18454_amd", "csrc", "palsgd.hip")
-    text = open(path, "r").read().split("// ======== end of the local-update kernel", 1)[0]
+    csrc = csrc or os.path.join(ROOT, "paper_2504_18454_amd", "csrc")
+    text = "".join(open(os.path.join(csrc, name), "r").read() for name in ("device_common.h", "step_kernel.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     text = re.sub(r"//[^\n]*", "", text)
     text = re.sub(r"\s+", "", text)

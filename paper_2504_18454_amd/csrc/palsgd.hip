@@ -1,5 +1,12 @@
-// PALSGD parameter-update path for MI355X (gfx950, CDNA4): HIP kernels and the C ABI
-// declared in include/palsgd.h.
+// PALSGD parameter-update path for MI355X (gfx950, CDNA4): the C ABI declared in
+// include/palsgd.h (context, argument checks, launches) over the HIP kernels of this
+// directory, which this one translation unit includes:
+//   device_common.h     vector type, tile, per-slot scalars, streaming loads/stores
+//   step_kernel.h       local update of all K workers (both branches) in one launch
+//   outer_kernels.h     outer step, its fusion with the last local update, init
+//   warmup_kernels.h    DDP warm-up step and the broadcast that ends the warm-up
+//   reduce_kernels.h    gradient norms, consensus-distance diagnostics
+//   schedule_kernels.h  branch draws, device-resident schedule for HIP graphs
 //
 // All kernels are bound by HBM bandwidth (about one flop per byte moved; the correctly
 // rounded divide and the square root cost nothing measurable), so the design rules are:
@@ -44,662 +51,16 @@
 #include <vector>
 
 #include "../../include/palsgd.h"
+#include "device_common.h"
+#include "outer_kernels.h"
+#include "reduce_kernels.h"
+#include "schedule_kernels.h"
+#include "step_kernel.h"
+#include "warmup_kernels.h"
+
+using namespace palsgd_dev;
 
 namespace {
-
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u2 __attribute__((ext_vector_type(2)));
-
-constexpr int kWave = 64;            // lanes of a wavefront = threads of a streaming workgroup
-constexpr int kTile = kWave * 4;     // elements a wavefront covers with one 16-byte group per lane
-constexpr int kThreads = 256;        // workgroup of the LDS-staged outer variant and of init
-constexpr uint32_t kLdsPerCUDefault = 160u * 1024u;  // gfx950; the device is asked at the first launch
-constexpr uint32_t kInflightDefault = 72u * 1024u;  // bytes of loads+stores in flight per CU
-
-// Per-launch, per-slot scalars; slot s of the grid's y dimension works on row `replica`.
-struct Slot {
-    float lr;        // alpha_t / (1-p), the learning rate handed to InnerOPT
-    float c1;        // AdamW: lr / (1 - beta1^tau)
-    float c2;        // AdamW: 1 / sqrt(1 - beta2^tau)
-    float beta_mix;  // alpha_t * eta_t / p
-    float gscale;    // multiplier on the gradient
-    uint32_t replica;
-    uint32_t mix;    // 1: pseudo-synchronization step, 0: gradient step
-};
-struct StepArgs {
-    Slot s[PALSGD_MAX_K];
-};
-
-struct Hyper {
-    float beta1, beta2, eps, momentum;
-    float wd;        // weight decay when every tensor has the same multiplier
-    int nesterov;    // SGD-momentum: step along d + mu * buf instead of buf
-};
-
-__device__ __forceinline__ f4 ld4(const float* p) { return __builtin_nontemporal_load((const f4*)p); }
-// Streaming store: non-temporal and agent scope ("sc1 nt").  The compiler's non-temporal
-// store builtin emits "nt" alone; the agent-scope variant measured 2 % faster on the 7-stream
-// update and is what every write-once store of this file uses.
-__device__ __forceinline__ void st4(float* p, f4 v) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
-}
-// read that other workgroups will want again soon (the global model during mixing)
-__device__ __forceinline__ f4 ld4_cached(const float* p) { return *(const f4*)p; }
-
-template <int GDT>
-struct GradLoad;
-template <>
-struct GradLoad<PALSGD_GRAD_F32> {
-    typedef f4 raw;
-    static __device__ __forceinline__ raw load(const void* g, uint64_t e) {
-        return __builtin_nontemporal_load((const f4*)((const float*)g + e));
-    }
-    static __device__ __forceinline__ f4 widen(raw r) { return r; }
-};
-template <>
-struct GradLoad<PALSGD_GRAD_BF16> {
-    typedef u2 raw;  // four bf16 values
-    static __device__ __forceinline__ raw load(const void* g, uint64_t e) {
-        return __builtin_nontemporal_load((const u2*)((const uint16_t*)g + e));
-    }
-    // bf16 is the upper half of an fp32: widening is a shift, exact
-    static __device__ __forceinline__ f4 widen(raw r) {
-        f4 o;
-        o.x = __uint_as_float(r.x << 16);
-        o.y = __uint_as_float(r.x & 0xFFFF0000u);
-        o.z = __uint_as_float(r.y << 16);
-        o.w = __uint_as_float(r.y & 0xFFFF0000u);
-        return o;
-    }
-};
-
-// AdamW on four elements (Loshchilov & Hutter Alg. 2; Sec. 4.3 of the paper names it as
-// InnerOPT).  c1 = lr/(1-b1^tau), c2 = 1/sqrt(1-b2^tau), decay = lr*wd.
-__device__ __forceinline__ void adamw4(f4& x, f4& m, f4& v, f4 g, const Hyper& h, float c1, float c2,
-                                       float decay) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float mi = fmaf(h.beta1, m[i], (1.0f - h.beta1) * g[i]);
-        float vi = fmaf(h.beta2, v[i], (1.0f - h.beta2) * g[i] * g[i]);
-        float denom = fmaf(sqrtf(vi), c2, h.eps);
-        // the whole step first (small, so its rounding is far below an ulp of x), then ONE rounding of x
-        x[i] = x[i] - fmaf(c1, mi / denom, decay * x[i]);
-        m[i] = mi;
-        v[i] = vi;
-    }
-}
-
-// SGD with momentum on four elements: d = g + wd x; buf = mu buf + d; x -= lr buf, or in the
-// Nesterov form x -= lr (d + mu buf).
-__device__ __forceinline__ void sgdm4(f4& x, f4& b, f4 g, const Hyper& h, float lr, float wd) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float d = fmaf(wd, x[i], g[i]);
-        float bi = fmaf(h.momentum, b[i], d);
-        float dir = h.nesterov ? fmaf(h.momentum, bi, d) : bi;
-        x[i] = fmaf(-lr, dir, x[i]);
-        b[i] = bi;
-    }
-}
-
-// Local update of step t.  Grid: x = tile of the row, y = slot.  A gradient-step wavefront
-// takes one tile (256 elements: 6.5-7 KiB of traffic); a mixing wavefront takes two (6 KiB),
-// so that both kinds keep about the same number of bytes in flight.
-// TAB: weight decay comes from a table with one entry per 64 elements of a row.
-// DEV: the per-slot scalars come from device memory (dev_slots, written by plan_kernel for
-// this step) instead of the kernel arguments.  A compile-time switch: selecting the source
-// at run time turns the scalar loads and the uniform branch into vector ones (-10 %).
-template <int INNER, int GDT, bool TAB, bool DEV>
-__global__ __launch_bounds__(kWave) void step_kernel(const StepArgs args, const Slot* __restrict__ dev_slots,
-                                                     const float* __restrict__ wd_tab, float* __restrict__ X, float* __restrict__ M,
-                                                     float* __restrict__ V, const void* __restrict__ G,
-                                                     const float* __restrict__ XG,
-                                                     const float* __restrict__ clip_scale, uint64_t n,
-                                                     uint64_t row_stride, Hyper h) {
-    const Slot sl = DEV ? dev_slots[blockIdx.y] : args.s[blockIdx.y];
-    const uint64_t row = (uint64_t)sl.replica * row_stride;
-    const uint32_t lane4 = threadIdx.x * 4;
-
-    if (sl.mix) {
-        // pseudo-synchronization step: x_k <- x_k - beta (x_k - x)     (Sec. 4.1, second equation)
-        const uint64_t e0 = (uint64_t)blockIdx.x * (2 * kTile) + lane4;
-        if (e0 >= n) return;
-        const uint64_t e1 = e0 + kTile;
-        const bool two = e1 < n;
-        float* __restrict__ x = X + row;
-        f4 x0 = ld4(x + e0), g0 = ld4_cached(XG + e0), x1, g1;
-        if (two) {
-            x1 = ld4(x + e1);
-            g1 = ld4_cached(XG + e1);
-        }
-        st4(x + e0, x0 - sl.beta_mix * (x0 - g0));
-        if (two) st4(x + e1, x1 - sl.beta_mix * (x1 - g1));
-        return;
-    }
-
-    // gradient step: x_k <- InnerOPT(x_k, g_k, alpha/(1-p))             (Sec. 4.1, first equation)
-    const uint64_t e = (uint64_t)blockIdx.x * kTile + lane4;
-    if (e >= n) return;
-    const uint64_t o = row + e;
-    typedef GradLoad<GDT> GL;
-    typename GL::raw gr = GL::load(G, o);
-    f4 xv = ld4(X + o), mv = ld4(M + o);
-    const float wd = TAB ? wd_tab[e >> 6] : h.wd;
-    // per-replica gradient multiplier: the caller's, times the clipping scale left on the device
-    const float gs = clip_scale ? sl.gscale * clip_scale[sl.replica] : sl.gscale;
-    if (INNER == PALSGD_INNER_ADAMW) {
-        f4 vv = ld4(V + o);
-        f4 g = GL::widen(gr) * gs;
-        adamw4(xv, mv, vv, g, h, sl.c1, sl.c2, sl.lr * wd);
-        st4(X + o, xv);
-        st4(M + o, mv);
-        st4(V + o, vv);
-    } else {
-        f4 g = GL::widen(gr) * gs;
-        sgdm4(xv, mv, g, h, sl.lr, wd);
-        st4(X + o, xv);
-        st4(M + o, mv);
-    }
-}
-
-// ======== end of the local-update kernel and its helpers ========
-
-struct OuterArgs {
-    float inv_k, lr, mu;
-    int nesterov;
-};
-
-// OuterOPT on four elements given dsum = sum_k (x - x_k) (Sec. 4.2; Sec. 4.3).  Summing the
-// differences instead of the models keeps Delta accurate to fp32 relative to its own size
-// and makes it exactly zero when the workers equal the global model.
-__device__ __forceinline__ f4 outer4(f4 dsum, f4 xg, f4& om, const OuterArgs& a) {
-    f4 delta = dsum * a.inv_k;                     // Delta = mean_k (x - x_k)
-    om = a.mu * om + delta;
-    f4 dir = a.nesterov ? delta + a.mu * om : om;
-    return xg - a.lr * dir;
-}
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
-    return v;  // lane 0 holds the sum
-}
-
-// Variant 1: one wavefront per tile; each lane owns four consecutive elements and walks the
-// K rows in ascending order, eight independent loads in flight at a time.
-// DIAG: also leaves, per wavefront, the partial sums of sum_k |x - x_k|^2 and |Delta|^2
-// (App. A.3) taken from the values already in registers: no extra HBM reads.
-template <bool DIAG>
-__global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X, float* __restrict__ XG,
-                                                           float* __restrict__ OM, uint64_t n,
-                                                           uint64_t row_stride, uint32_t K, OuterArgs a,
-                                                           float* __restrict__ partial, uint32_t n_part) {
-    const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
-    const bool active = e < n;  // no early exit: every lane takes part in the shuffles
-    f4 sum = {0.f, 0.f, 0.f, 0.f}, sq = {0.f, 0.f, 0.f, 0.f};
-    if (active) {
-        f4 xg = ld4(XG + e);
-        f4 om = ld4(OM + e);
-        for (uint32_t k0 = 0; k0 < K; k0 += 8) {
-            f4 t[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (k0 + u < K) t[u] = ld4(X + (uint64_t)(k0 + u) * row_stride + e);
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (k0 + u < K) {
-                    f4 d = xg - t[u];
-                    sum += d;
-                    if (DIAG) sq += d * d;
-                }
-        }
-        f4 xn = outer4(sum, xg, om, a);
-        st4(XG + e, xn);
-        st4(OM + e, om);
-        for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
-    }
-    if (DIAG) {
-        const f4 delta = sum * a.inv_k;
-        const f4 dd = delta * delta;
-        float xi = wave_sum((sq.x + sq.y) + (sq.z + sq.w));
-        float d2 = wave_sum((dd.x + dd.y) + (dd.z + dd.w));
-        if (threadIdx.x == 0) {
-            partial[blockIdx.x] = xi;
-            partial[n_part + blockIdx.x] = d2;
-        }
-    }
-}
-
-// Last local update of a window fused with the outer step (Alg. 1, step t with (t+1) mod H = 0):
-// a wavefront owns a tile of ALL K rows.  It takes the replicas in ascending order, four at a
-// time (their loads in flight together), applies each replica's branch, stores the InnerOPT
-// state, keeps the new x_k in registers only and adds x - x_k to the outer gradient; then
-// OuterOPT and the restart stores.  Against the two separate launches this saves writing the
-// K rows of X in the local update and reading them back in the outer step (8K of 34K+16 bytes
-// per element with AdamW).  Slot s of `args` is replica s.  The arithmetic, its order and its
-// roundings are those of step_kernel followed by outer_kernel_walk: results are bit-identical.
-constexpr int kSyncBatch = 4;
-
-template <int INNER, int GDT, bool TAB>
-__global__ __launch_bounds__(kWave) void sync_step_kernel(const StepArgs args, const float* __restrict__ wd_tab,
-                                                          float* __restrict__ X, float* __restrict__ M,
-                                                          float* __restrict__ V, const void* __restrict__ G,
-                                                          float* __restrict__ XG, float* __restrict__ OM,
-                                                          const float* __restrict__ clip_scale, uint64_t n,
-                                                          uint64_t row_stride, uint32_t K, Hyper h, OuterArgs a) {
-    const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
-    if (e >= n) return;
-    typedef GradLoad<GDT> GL;
-    const f4 xg = ld4(XG + e);
-    f4 om = ld4(OM + e);
-    const float wd = TAB ? wd_tab[e >> 6] : h.wd;
-    f4 dsum = {0.f, 0.f, 0.f, 0.f};
-    for (uint32_t k0 = 0; k0 < K; k0 += kSyncBatch) {
-        typename GL::raw gr[kSyncBatch];
-        f4 xv[kSyncBatch], mv[kSyncBatch], vv[kSyncBatch];
-#pragma unroll
-        for (int u = 0; u < kSyncBatch; ++u) {
-            if (k0 + u < K) {
-                const uint64_t o = (uint64_t)(k0 + u) * row_stride + e;
-                xv[u] = ld4(X + o);
-                if (!args.s[k0 + u].mix) {
-                    gr[u] = GL::load(G, o);
-                    mv[u] = ld4(M + o);
-                    if (INNER == PALSGD_INNER_ADAMW) vv[u] = ld4(V + o);
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kSyncBatch; ++u) {
-            if (k0 + u < K) {
-                const Slot sl = args.s[k0 + u];
-                const uint64_t o = (uint64_t)(k0 + u) * row_stride + e;
-                if (sl.mix) {
-                    xv[u] = xv[u] - sl.beta_mix * (xv[u] - xg);
-                } else {
-                    const float gs = clip_scale ? sl.gscale * clip_scale[sl.replica] : sl.gscale;
-                    const f4 g = GL::widen(gr[u]) * gs;
-                    if (INNER == PALSGD_INNER_ADAMW) {
-                        adamw4(xv[u], mv[u], vv[u], g, h, sl.c1, sl.c2, sl.lr * wd);
-                        st4(V + o, vv[u]);
-                    } else {
-                        sgdm4(xv[u], mv[u], g, h, sl.lr, wd);
-                    }
-                    st4(M + o, mv[u]);
-                }
-                dsum += xg - xv[u];
-            }
-        }
-    }
-    const f4 xn = outer4(dsum, xg, om, a);
-    st4(XG + e, xn);
-    st4(OM + e, om);
-    for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
-}
-
-// Variant 2: a workgroup owns a tile of 4 x 256 elements.  Wave w sums the replicas
-// k = w, w+4, ... for the whole tile, the four partial sums per element meet in LDS,
-// and wave w finishes sub-tile w: fixed-order combine, OuterOPT, stores.  Puts 4*ceil(K/4)
-// row loads in flight per lane before the first add.
-__global__ __launch_bounds__(kThreads) void outer_kernel_lds(float* __restrict__ X, float* __restrict__ XG,
-                                                             float* __restrict__ OM, uint64_t n4,
-                                                             uint64_t row_stride, uint32_t K, OuterArgs a) {
-    __shared__ f4 part[4][4][64];  // [wave][sub-tile][lane], 16 KiB
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const uint64_t tile4 = (uint64_t)blockIdx.x * 256;  // first float4 of the tile
-    f4 acc[4], xgt[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        acc[s] = (f4){0.f, 0.f, 0.f, 0.f};
-        uint64_t i = tile4 + s * 64 + lane;
-        xgt[s] = i < n4 ? ld4_cached(XG + i * 4) : (f4){0.f, 0.f, 0.f, 0.f};
-    }
-    for (uint32_t k = w; k < K; k += 4) {
-        const float* row = X + (uint64_t)k * row_stride;
-        f4 t[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            uint64_t i = tile4 + s * 64 + lane;
-            t[s] = i < n4 ? ld4(row + i * 4) : (f4){0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) acc[s] += xgt[s] - t[s];
-    }
-#pragma unroll
-    for (int s = 0; s < 4; ++s) part[w][s][lane] = acc[s];
-    __syncthreads();
-    const uint64_t i = tile4 + w * 64 + lane;
-    if (i < n4) {
-        const uint64_t e = i * 4;
-        f4 sum = ((part[0][w][lane] + part[1][w][lane]) + part[2][w][lane]) + part[3][w][lane];
-        f4 xg = w == 0 ? xgt[0] : (w == 1 ? xgt[1] : (w == 2 ? xgt[2] : xgt[3]));
-        f4 om = ld4(OM + e);
-        f4 xn = outer4(sum, xg, om, a);
-        st4(XG + e, xn);
-        st4(OM + e, om);
-        for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
-    }
-}
-
-// x_k^(0) <- x^(0) for all k, XG <- x^(0), cleared moments (Alg. 1, first line of the worker loop).
-__global__ __launch_bounds__(kThreads) void init_kernel(const float* __restrict__ x0, float* __restrict__ X,
-                                                        float* __restrict__ M, float* __restrict__ V,
-                                                        float* __restrict__ XG, float* __restrict__ OM,
-                                                        uint64_t n4, uint64_t row_stride, uint32_t K) {
-    uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n4) return;
-    uint64_t e = i * 4;
-    f4 v = *(const f4*)(x0 + e);
-    f4 z = {0.f, 0.f, 0.f, 0.f};
-    st4(XG + e, v);
-    st4(OM + e, z);
-    for (uint32_t k = 0; k < K; ++k) {
-        uint64_t r = (uint64_t)k * row_stride + e;
-        st4(X + r, v);
-        st4(M + r, z);
-        if (V) st4(V + r, z);
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// Device-resident schedule, for callers that capture their training step in a HIP graph: a
-// captured launch keeps its arguments, so everything that changes from step to step (the
-// step index t, the branch draws, each worker's InnerOPT step count and bias corrections,
-// alpha_t and eta_t) lives in device memory and is advanced by plan_kernel, one lane per
-// worker, right before each local update.
-struct DevSchedule {
-    uint64_t t;                  // index of the next step
-    uint64_t tau[PALSGD_MAX_K];  // gradient steps taken per worker
-    Slot slot[PALSGD_MAX_K];     // scalars of the step about to run
-};
-
-struct PlanArgs {
-    uint64_t seed;
-    double p, beta1, beta2;
-    uint32_t K, threshold, adamw;
-};
-
-// SplitMix64 output function as a counter hash (Steele, Lea, Flood 2014), top 24 bits.
-__host__ __device__ inline uint32_t draw_u24(uint64_t seed, uint64_t t, uint32_t k, uint32_t K) {
-    uint64_t z = seed + (t * (uint64_t)K + k + 1ull) * 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return (uint32_t)(z >> 40);
-}
-
-__global__ __launch_bounds__(kWave) void plan_kernel(DevSchedule* __restrict__ s, const float* __restrict__ alpha_eta,
-                                                     PlanArgs a) {
-    const uint32_t k = threadIdx.x;
-    const uint64_t t = s->t;
-    const double alpha = (double)alpha_eta[0], eta = (double)alpha_eta[1];
-    if (k < a.K) {
-        Slot sl;
-        sl.replica = k;
-        sl.gscale = 1.0f;
-        sl.lr = sl.c1 = sl.c2 = sl.beta_mix = 0.0f;
-        sl.mix = draw_u24(a.seed, t, k, a.K) < a.threshold ? 1u : 0u;
-        if (sl.mix) {
-            sl.beta_mix = (float)(alpha * eta / a.p);        // a.p > 0 whenever a draw can fire
-        } else {
-            const uint64_t tau = s->tau[k] + 1;
-            s->tau[k] = tau;
-            const double lr = alpha / (1.0 - a.p);
-            sl.lr = (float)lr;
-            if (a.adamw) {
-                sl.c1 = (float)(lr / (1.0 - pow(a.beta1, (double)tau)));
-                sl.c2 = (float)(1.0 / sqrt(1.0 - pow(a.beta2, (double)tau)));
-            }
-        }
-        s->slot[k] = sl;
-    }
-    __syncthreads();  // every lane has read t
-    if (k == 0) s->t = t + 1;
-}
-
-struct TauArgs {
-    uint64_t tau[PALSGD_MAX_K];
-};
-
-__global__ void schedule_set_kernel(DevSchedule* __restrict__ s, uint64_t t0, TauArgs a) {
-    const uint32_t k = threadIdx.x;
-    if (k < PALSGD_MAX_K) s->tau[k] = a.tau[k];
-    if (k == 0) s->t = t0;
-}
-
-// ---------------------------------------------------------------------------------------
-// DDP step of the warm-up phase (Sec. 3.1: All-Reduce of the gradient, then the optimizer
-// update, identical on every worker; Sec. 4.3).  One wavefront per tile: weighted mean of the
-// K gradient rows (k ascending, eight loads in flight), InnerOPT on the common model (read
-// from XG) with the common state (replica 0's), model stored to XG and to the first x_rows
-// rows of X (K, or 0 when the rows are left to the end of the warm-up), state to replica 0
-// only: the other replicas' copies are made once, when the warm-up ends.
-struct DdpArgs {
-    float w[PALSGD_MAX_K];  // grad_scale[k]
-    float inv_k, lr, c1, c2;
-};
-
-template <int INNER, int GDT, bool TAB>
-__global__ __launch_bounds__(kWave) void ddp_kernel(const DdpArgs a, const float* __restrict__ wd_tab,
-                                                    float* __restrict__ X, float* __restrict__ M,
-                                                    float* __restrict__ V, const void* __restrict__ G,
-                                                    float* __restrict__ XG,
-                                                    const float* __restrict__ clip_scale, uint64_t n,
-                                                    uint64_t row_stride, uint32_t K, uint32_t x_rows, Hyper h) {
-    const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
-    if (e >= n) return;
-    typedef GradLoad<GDT> GL;
-    f4 xv = ld4(XG + e), mv = ld4(M + e), vv;
-    if (INNER == PALSGD_INNER_ADAMW) vv = ld4(V + e);
-    f4 sum = {0.f, 0.f, 0.f, 0.f};
-    for (uint32_t k0 = 0; k0 < K; k0 += 8) {
-        typename GL::raw t[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (k0 + u < K) t[u] = GL::load(G, (uint64_t)(k0 + u) * row_stride + e);
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (k0 + u < K) sum += GL::widen(t[u]) * a.w[k0 + u];
-    }
-    // averaged gradient, times the clipping scale of its norm if one was left on the device
-    const f4 g = sum * (clip_scale ? a.inv_k * clip_scale[0] : a.inv_k);
-    const float wd = TAB ? wd_tab[e >> 6] : h.wd;
-    if (INNER == PALSGD_INNER_ADAMW)
-        adamw4(xv, mv, vv, g, h, a.c1, a.c2, a.lr * wd);
-    else
-        sgdm4(xv, mv, g, h, a.lr, wd);
-    st4(XG + e, xv);
-    st4(M + e, mv);  // the common InnerOPT state lives in replica 0 during the warm-up
-    if (INNER == PALSGD_INNER_ADAMW) st4(V + e, vv);
-    for (uint32_t k = 0; k < x_rows; ++k) st4(X + (uint64_t)k * row_stride + e, xv);
-}
-
-// End of the warm-up: replicas 1..K-1 take over the common InnerOPT state of replica 0
-// (M, and V unless NULL), and all K rows of X take the common model from XG (unless X is
-// NULL: the DDP steps kept the rows current themselves).
-__global__ __launch_bounds__(kWave) void warmup_broadcast_kernel(float* __restrict__ M, float* __restrict__ V,
-                                                                 float* __restrict__ X, const float* __restrict__ XG,
-                                                                 uint64_t n, uint64_t row_stride, uint32_t K) {
-    const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
-    if (e >= n) return;
-    f4 mv, vv, xv;
-    if (M) mv = ld4(M + e);
-    if (V) vv = ld4(V + e);
-    if (X) {
-        xv = ld4(XG + e);
-        st4(X + e, xv);
-    }
-    for (uint32_t k = 1; k < K; ++k) {
-        const uint64_t o = (uint64_t)k * row_stride + e;
-        if (M) st4(M + o, mv);
-        if (V) st4(V + o, vv);
-        if (X) st4(X + o, xv);
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// Reductions to scalars: lane-local accumulation, a shuffle tree inside the wavefront, one
-// partial per wavefront in device scratch, and a second single-workgroup pass that adds the
-// partials in double in a fixed order (deterministic run to run).
-constexpr int kNormTiles = 16;  // tiles a wavefront of the norm kernel walks: one partial per 4096 elements
-constexpr int kDiagTiles = 8;   // same for the diagnostics kernel: one partial pair per 2048 elements
-
-// Sum of squares of one replica's gradient row, per wavefront (App. B: gradient clipping).
-template <int GDT>
-__global__ __launch_bounds__(kWave) void sumsq_kernel(const void* __restrict__ G, float* __restrict__ partial,
-                                                      uint64_t n, uint64_t row_stride, uint32_t per_row) {
-    typedef GradLoad<GDT> GL;
-    const uint64_t base = (uint64_t)blockIdx.x * (kTile * kNormTiles) + threadIdx.x * 4;
-    const uint64_t row = (uint64_t)blockIdx.y * row_stride;
-    float acc = 0.f;
-    typename GL::raw r[kNormTiles];  // all loads of the wavefront are issued before the first use
-#pragma unroll
-    for (int u = 0; u < kNormTiles; ++u) {
-        const uint64_t e = base + (uint64_t)u * kTile;
-        if (e < n) r[u] = GL::load(G, row + e);
-    }
-#pragma unroll
-    for (int u = 0; u < kNormTiles; ++u) {
-        const uint64_t e = base + (uint64_t)u * kTile;
-        if (e < n) {
-            f4 g = GL::widen(r[u]);
-            acc += (g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w);
-        }
-    }
-    acc = wave_sum(acc);
-    if (threadIdx.x == 0) partial[(uint64_t)blockIdx.y * per_row + blockIdx.x] = acc;
-}
-
-// Sum of squares of the averaged gradient (1/K) sum_k w_k g_k, per wavefront of two tiles
-// (clipping in the DDP phase, where the optimizer sees the averaged gradient, Sec. 3.1).
-constexpr int kMeanTiles = 2;
-template <int GDT>
-__global__ __launch_bounds__(kWave) void sumsq_mean_kernel(const void* __restrict__ G, const DdpArgs a,
-                                                           float* __restrict__ partial, uint64_t n,
-                                                           uint64_t row_stride, uint32_t K) {
-    typedef GradLoad<GDT> GL;
-    const uint64_t base = (uint64_t)blockIdx.x * (kTile * kMeanTiles) + threadIdx.x * 4;
-    float acc = 0.f;
-#pragma unroll
-    for (int u = 0; u < kMeanTiles; ++u) {
-        const uint64_t e = base + (uint64_t)u * kTile;
-        if (e < n) {
-            f4 sum = {0.f, 0.f, 0.f, 0.f};
-            for (uint32_t k0 = 0; k0 < K; k0 += 8) {
-                typename GL::raw t[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    if (k0 + q < K) t[q] = GL::load(G, (uint64_t)(k0 + q) * row_stride + e);
-#pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    if (k0 + q < K) sum += GL::widen(t[q]) * a.w[k0 + q];
-            }
-            const f4 g = sum * a.inv_k;
-            acc += (g.x * g.x + g.y * g.y) + (g.z * g.z + g.w * g.w);
-        }
-    }
-    acc = wave_sum(acc);
-    if (threadIdx.x == 0) partial[blockIdx.x] = acc;
-}
-
-// Fixed-order sum of `count` values in double by one workgroup; every thread returns the total.
-template <typename T>
-__device__ double block_sum(const T* __restrict__ v, uint32_t count, double* lds) {
-    double acc = 0.0;
-    for (uint32_t j = threadIdx.x; j < count; j += 4 * kThreads) {  // four independent loads in flight
-        T t[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) t[q] = j + q * kThreads < count ? v[j + q * kThreads] : (T)0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) acc += (double)t[q];
-    }
-    lds[threadIdx.x] = acc;
-    __syncthreads();
-    for (int s = kThreads / 2; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) lds[threadIdx.x] += lds[threadIdx.x + s];
-        __syncthreads();
-    }
-    double total = lds[0];
-    __syncthreads();
-    return total;
-}
-
-constexpr uint32_t kFold = 128;  // second-stage workgroups per series of partial sums
-
-// Second stage: series y has `count` float partials; workgroup x adds its contiguous slice in double.
-__global__ __launch_bounds__(kThreads) void fold_kernel(const float* __restrict__ partial, uint32_t count,
-                                                        double* __restrict__ fold) {
-    __shared__ double lds[kThreads];
-    const uint32_t slice = (count + kFold - 1) / kFold;
-    const uint32_t begin = blockIdx.x * slice;
-    const uint32_t len = begin >= count ? 0u : (count - begin < slice ? count - begin : slice);
-    double total = block_sum(partial + (uint64_t)blockIdx.y * count + begin, len, lds);
-    if (threadIdx.x == 0) fold[blockIdx.y * kFold + blockIdx.x] = total;
-}
-
-// norm_k = sqrt(sum of squares); scale_k = min(1, max_norm / (norm_k + 1e-6)).  One workgroup per replica.
-__global__ __launch_bounds__(kThreads) void clip_finish_kernel(const double* __restrict__ fold, float max_norm,
-                                                               float* __restrict__ scale,
-                                                               float* __restrict__ norms_out) {
-    __shared__ double lds[kThreads];
-    const uint32_t k = blockIdx.x;
-    double total = block_sum(fold + k * kFold, kFold, lds);
-    if (threadIdx.x == 0) {
-        double norm = sqrt(total);
-        double c = (double)max_norm / (norm + 1e-6);
-        scale[k] = (float)(c < 1.0 ? c : 1.0);
-        if (norms_out) norms_out[k] = (float)norm;
-    }
-}
-
-// Consensus distance and outer-gradient norm (App. A.3): per wavefront, partial sums of
-// sum_k |x_k - x|^2 and of |x - mean_k x_k|^2.
-__global__ __launch_bounds__(kWave) void diag_kernel(const float* __restrict__ X, const float* __restrict__ XG,
-                                                     float* __restrict__ partial, uint64_t n, uint64_t row_stride,
-                                                     uint32_t K, float inv_k, uint32_t n_part) {
-    const uint64_t base = (uint64_t)blockIdx.x * (kTile * kDiagTiles) + threadIdx.x * 4;
-    float xi = 0.f, d2 = 0.f;
-    for (int u = 0; u < kDiagTiles; ++u) {
-        const uint64_t e = base + (uint64_t)u * kTile;
-        if (e >= n) break;
-        const f4 xg = ld4(XG + e);
-        f4 sum = {0.f, 0.f, 0.f, 0.f}, sq = {0.f, 0.f, 0.f, 0.f};
-        for (uint32_t k0 = 0; k0 < K; k0 += 8) {
-            f4 t[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                if (k0 + q < K) t[q] = ld4(X + (uint64_t)(k0 + q) * row_stride + e);
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                if (k0 + q < K) {
-                    f4 d = xg - t[q];
-                    sq += d * d;
-                    sum += d;
-                }
-        }
-        const f4 delta = sum * inv_k;
-        const f4 dd = delta * delta;
-        xi += (sq.x + sq.y) + (sq.z + sq.w);
-        d2 += (dd.x + dd.y) + (dd.z + dd.w);
-    }
-    xi = wave_sum(xi);
-    d2 = wave_sum(d2);
-    if (threadIdx.x == 0) {
-        partial[blockIdx.x] = xi;
-        partial[n_part + blockIdx.x] = d2;
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void diag_finish_kernel(const double* __restrict__ fold, float inv_k,
-                                                               float* __restrict__ out) {
-    __shared__ double lds[kThreads];
-    double xi = block_sum(fold, kFold, lds);
-    double d2 = block_sum(fold + kFold, kFold, lds);
-    if (threadIdx.x == 0) {
-        out[0] = (float)(xi * (double)inv_k);
-        out[1] = (float)d2;
-    }
-}
 
 // ======== host side: context, argument checks, launches ========
 
