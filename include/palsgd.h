@@ -252,6 +252,12 @@ const char *palsgd_last_error(const palsgd_ctx *ctx);
  * must have synchronised work that still uses the table).  NULL is accepted. */
 void palsgd_destroy(palsgd_ctx *ctx);
 
+/* OuterOPT learning rate for the outer steps that follow (App. B: the ImageNet runs schedule
+ * the outer learning rate, warm-up then cosine decay), replacing the value given at
+ * palsgd_init.  Host state only: a launch that was captured into a HIP graph keeps the
+ * value it was captured with.  EINVAL unless finite and >= 0. */
+palsgd_status palsgd_set_outer_lr(palsgd_ctx *ctx, float outer_lr);
+
 /* Launch-shape knobs for tuning and tests.  The kernels are throttled to a number of
  * resident wavefronts per compute unit (fewer than the hardware allows streams better);
  * step_waves_per_cu / outer_waves_per_cu override the built-in choice (0 = built-in,

@@ -197,6 +197,10 @@ class OracleState:
         s.n_outer = 0
         self.s = s
 
+    def set_outer_lr(self, outer_lr):
+        """OuterOPT learning rate of the outer steps that follow (a schedule on it, App. B)."""
+        self.s.outer_lr = float(np.float32(outer_lr))
+
     @property
     def n_outer(self):
         return int(self.s.n_outer)

@@ -27,7 +27,7 @@ EXPORTS = ("palsgd_layout", "palsgd_init", "palsgd_draw", "palsgd_inner_step", "
            "palsgd_last_error", "palsgd_destroy", "palsgd_set_tuning", "palsgd_ddp_step",
            "palsgd_clip_grad_norm", "palsgd_diagnostics", "palsgd_outer_step_diag", "palsgd_capturable_begin",
            "palsgd_step_capturable", "palsgd_capturable_end", "palsgd_ddp_finish", "palsgd_clip_mean_grad_norm", "palsgd_step_sync",
-           "palsgd_ddp_step_shared")
+           "palsgd_ddp_step_shared", "palsgd_set_outer_lr")
 
 
 class PalsgdError(RuntimeError):
@@ -108,6 +108,8 @@ def lib() -> C.CDLL:
         L.palsgd_last_error.argtypes = [vp]
         L.palsgd_destroy.restype = None
         L.palsgd_destroy.argtypes = [vp]
+        L.palsgd_set_outer_lr.restype = st
+        L.palsgd_set_outer_lr.argtypes = [vp, f]
         L.palsgd_set_tuning.restype = st
         L.palsgd_set_tuning.argtypes = [vp, u32, u32, u32]
         _lib = L
@@ -277,6 +279,9 @@ class Palsgd:
     def palsgd_set_state(self, tau, n_outer):
         arr = (C.c_uint64 * self.K)(*[int(v) for v in tau])
         _check(lib().palsgd_set_state(self._ctx, arr, int(n_outer)), self._ctx)
+
+    def palsgd_set_outer_lr(self, outer_lr):
+        _check(lib().palsgd_set_outer_lr(self._ctx, outer_lr), self._ctx)
 
     def palsgd_set_tuning(self, step_waves_per_cu=0, outer_waves_per_cu=0, outer_variant=0):
         _check(lib().palsgd_set_tuning(self._ctx, int(step_waves_per_cu), int(outer_waves_per_cu),

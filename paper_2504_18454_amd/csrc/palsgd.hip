@@ -891,6 +891,19 @@ void palsgd_destroy(palsgd_ctx* ctx) {
     delete ctx;
 }
 
+palsgd_status palsgd_set_outer_lr(palsgd_ctx* ctx, float outer_lr) {
+    if (!ctx) {
+        set_error(g_error, "palsgd_set_outer_lr: NULL context");
+        return PALSGD_EINVAL;
+    }
+    if (!std::isfinite(outer_lr) || !(outer_lr >= 0.0f)) {
+        set_error(ctx->error, "palsgd_set_outer_lr: outer_lr must be finite and >= 0");
+        return PALSGD_EINVAL;
+    }
+    ctx->cfg.outer_lr = outer_lr;
+    return PALSGD_OK;
+}
+
 palsgd_status palsgd_set_tuning(palsgd_ctx* ctx, uint32_t step_waves_per_cu, uint32_t outer_waves_per_cu,
                                 uint32_t outer_variant) {
     if (!ctx) {

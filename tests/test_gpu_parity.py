@@ -85,6 +85,22 @@ def test_tuning_shapes_agree_with_oracle(variant, step_waves, outer_waves):
     r.close()
 
 
+def test_outer_learning_rate_schedule():
+    """The outer learning rate changes from one synchronisation to the next (App. B schedules it)."""
+    import math
+    r = _run(K=4, numels=RAGGED, p=0.2, H=2, seed=61, sigma=0.05, outer_lr=0.0, outer_momentum=0.9)
+    for window in range(6):
+        lr = 0.8 * (window + 1) / 3 if window < 3 else 0.4 * (1 + math.cos(math.pi * (window - 3) / 3))
+        r.ora.set_outer_lr(lr)
+        r.lib.palsgd_set_outer_lr(lr)
+        r.iterate(2, fused_sync=bool(window % 2))
+        r.compare()
+    from paper_2504_18454_amd import PalsgdError
+    with pytest.raises(PalsgdError):
+        r.lib.palsgd_set_outer_lr(float("nan"))
+    r.close()
+
+
 @pytest.mark.parametrize("nesterov,mu,lr", [(True, 0.9, 0.7), (False, 0.9, 0.7), (False, 0.0, 1.0)])
 def test_outer_variants(nesterov, mu, lr):
     r = _run(K=4, numels=[10000, 130], p=0.1, H=2, seed=16, outer_lr=lr, outer_momentum=mu, outer_nesterov=nesterov)
