@@ -191,8 +191,10 @@ palsgd_status palsgd_ddp_finish(palsgd_ctx *ctx, void *stream);
 /* Gradient clipping by the global L2 norm of each worker's gradient (App. B says the GPT-Neo runs
  * clip gradients; the paper prints no threshold): norm_k = |G[k]|_2 and
  * scale_k = min(1, max_norm / (norm_k + 1e-6)) are computed on the device, without a host
- * round trip.  The next palsgd_inner_step / palsgd_step of this context multiplies worker
- * k's gradient by scale_k (on top of grad_scale[k]) and forgets the scales.
+ * round trip.  The next palsgd_inner_step / palsgd_step / palsgd_step_sync /
+ * palsgd_step_capturable of this context multiplies worker k's gradient by scale_k (on top
+ * of grad_scale[k]) and forgets the scales, whether or not worker k (or any worker) takes
+ * the gradient branch in that step: they belong to that step's gradients.
  * norms_out_dev: device array of K floats that receives the norms, or NULL.
  * The first call allocates the library's reduction scratch (about P_padded/128 floats);
  * palsgd_clip_grad_norm, palsgd_diagnostics and palsgd_outer_step_diag share it and must

@@ -353,7 +353,10 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
     bool stepped[PALSGD_MAX_K];
     palsgd_status rc = plan_slots(c, who, t, alpha, eta, grad_scale, mask_override, do_grad, do_mix, args, n, stepped);
     if (rc != PALSGD_OK) return rc;
-    if (n == 0) return PALSGD_OK;
+    if (n == 0) {
+        if (do_grad) c->clip_armed = false;  // the scales belonged to this step's gradients, which nobody used
+        return PALSGD_OK;
+    }
     const uint32_t K = c->cfg.K;
     bool any_grad = false;
     for (uint32_t k = 0; k < K; ++k) any_grad = any_grad || stepped[k];
@@ -365,7 +368,7 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
     dispatch_step(c, args, nullptr, n, any_grad, clip, st);
     rc = check_launch(c, who);
     if (rc != PALSGD_OK) return rc;
-    if (clip) c->clip_armed = false;
+    if (do_grad) c->clip_armed = false;  // also when every worker mixed: the scales are this step's, not the next one's
     for (uint32_t k = 0; k < K; ++k)
         if (stepped[k]) c->tau[k] += 1;
     return PALSGD_OK;
@@ -539,7 +542,7 @@ palsgd_status palsgd_step_sync(palsgd_ctx* ctx, uint64_t t, float alpha_t, float
     else launch_sync_step<PALSGD_INNER_SGDM, PALSGD_GRAD_F32>(ctx, args, clip, a, st);
     rc = check_launch(ctx, "palsgd_step_sync");
     if (rc != PALSGD_OK) return rc;
-    if (clip) ctx->clip_armed = false;
+    ctx->clip_armed = false;
     for (uint32_t k = 0; k < K; ++k)
         if (stepped[k]) ctx->tau[k] += 1;
     ctx->n_outer += 1;
@@ -827,7 +830,7 @@ palsgd_status palsgd_step_capturable(palsgd_ctx* ctx, const float* alpha_eta_dev
     dispatch_step(ctx, none, ds->slot, ctx->cfg.K, true, clip, st);
     palsgd_status rc = check_launch(ctx, "palsgd_step_capturable");
     if (rc != PALSGD_OK) return rc;
-    if (clip) ctx->clip_armed = false;
+    ctx->clip_armed = false;
     return PALSGD_OK;
 }
 

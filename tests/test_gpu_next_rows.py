@@ -96,6 +96,21 @@ def test_ddp_shared_model_warmup(inner, grad_dtype, K, ender):
     r.close()
 
 
+def test_clipping_scales_belong_to_one_step():
+    """Scales computed for a step in which every worker mixes are dropped with that step: the next
+    gradient step must not see them."""
+    K = 3
+    r = _run(K=K, numels=[4096, 64, 700], p=0.3, H=50, seed=58, sigma=0.1, c_scale=0.25)
+    r.iterate(2)
+    r.iterate(1, clip=0.05, mask_fn=lambda t: [1] * K)         # clipping armed, nobody takes a gradient step
+    r.iterate(2, mask_fn=lambda t: [0] * K)                     # unclipped gradient steps
+    r.compare()
+    r.iterate(1, clip=0.05, mask_fn=lambda t: [1] * K, fused=False)   # same through the separate calls
+    r.iterate(2, mask_fn=lambda t: [0] * K)
+    r.compare()
+    r.close()
+
+
 def test_ddp_then_device_schedule():
     r = _run(K=4, numels=RAGGED, grad_dtype="bf16", p=0.25, H=3, seed=36, sigma=0.05)
     r.ddp_iterate(4)

@@ -1,0 +1,113 @@
+"""Random sequences of C-ABI calls against the same sequence on the oracle.
+
+Each entry point is covered on its own elsewhere; here they follow one another in seeded random order, so that
+what one call leaves for the next (the shared state of a DDP warm-up, armed clipping scales, the device-resident
+schedule, step counts handed back and forth) is exercised in orders nobody wrote down by hand."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+NUMELS = [3000, 64, 1, 5000, 333]
+
+
+def _run(**kw):
+    from parity import Run
+    return Run(**kw)
+
+
+def _identical_step_counts(r):
+    tau, _ = r.lib.palsgd_get_state()
+    return len(set(tau)) == 1
+
+
+# more seeds on request: PALSGD_SEQUENCE_SEEDS=300 python -m pytest tests/test_gpu_sequences.py -m gpu
+@pytest.mark.parametrize("seed", range(int(os.environ.get("PALSGD_SEQUENCE_SEEDS", "16"))))
+def test_random_call_sequence(seed):
+    from paper_2504_18454_amd import PalsgdError
+    rng = np.random.default_rng(1000 + seed)
+    K = int(rng.choice([1, 2, 3, 5, 8]))
+    inner, grad_dtype = [("adamw", "f32"), ("adamw", "bf16"), ("sgdm", "f32"), ("sgdm", "bf16")][seed % 4]
+    r = _run(K=K, numels=NUMELS, inner=inner, grad_dtype=grad_dtype, p=0.3, H=int(rng.choice([2, 3, 5])), seed=70 + seed,
+             sigma=0.1, c_scale=0.25, wd_mult=[1, 0, 1, 0.5, 1] if seed % 2 else None, row_extra=seed % 2,
+             inner_nesterov=bool(seed % 3 == 0))
+    dev = torch.device("cuda:0")
+    log = []
+    shared = False        # a DDP warm-up keeps the InnerOPT state (and with ddp_shared the model) once, until a later call needs the rows
+    for _ in range(40):
+        op = str(rng.choice(["step", "step", "step", "sync_fused", "split", "ddp", "ddp_shared", "clip_step", "clip_ddp",
+                             "diagnostics", "outer_now", "outer_diag_now", "state", "capturable", "finish", "outer_lr"]))
+        log.append(op)
+        try:
+            if op == "step":
+                r.iterate(int(rng.integers(1, 4)))
+            elif op == "sync_fused":
+                r.iterate(int(rng.integers(1, 4)), fused_sync=True)
+            elif op == "split":                                 # the two branches as separate calls
+                r.iterate(1, fused=False)
+            elif op in ("ddp", "ddp_shared", "clip_ddp"):
+                if not _identical_step_counts(r):               # the DDP step needs identical workers: refused, nothing changes
+                    with pytest.raises(PalsgdError) as e:
+                        r.lib.palsgd_ddp_step(r.t, r.alpha)
+                    assert e.value.status == 4
+                else:
+                    r.ddp_iterate(int(rng.integers(1, 3)), shared=op == "ddp_shared",
+                                  clip=0.5 if op == "clip_ddp" else None)
+                    shared = True
+            elif op == "clip_step":
+                r.iterate(1, clip=0.5)
+            elif op == "diagnostics":
+                r.compare_diagnostics()
+            elif op in ("outer_now", "outer_diag_now"):         # an outer step off the schedule is still an outer step
+                t = r.t - 1 if r.t else 0
+                if op == "outer_now":
+                    r.ora.outer_step()
+                    r.lib.palsgd_outer_step(t)
+                else:
+                    want = r.ora.diagnostics()
+                    r.ora.outer_step()
+                    out = torch.empty(2, dtype=torch.float32, device=dev)
+                    r.lib.palsgd_outer_step_diag(t, out)
+                    np.testing.assert_allclose(out.cpu().numpy(), want, rtol=2e-3, atol=1e-12)
+            elif op == "state":                                 # step counts out and in again
+                tau, n_outer = r.lib.palsgd_get_state()
+                r.lib.palsgd_set_state(tau, n_outer)
+            elif op == "finish":
+                r.lib.palsgd_ddp_finish()
+            elif op == "outer_lr":
+                lr = float(rng.choice([0.0, 0.2, 0.7, 1.0]))
+                r.ora.set_outer_lr(lr)
+                r.lib.palsgd_set_outer_lr(lr)
+            elif op == "capturable":                            # a few steps driven by the device-resident schedule
+                ae = torch.tensor([r.alpha, r.eta], dtype=torch.float32, device=dev)
+                r.lib.palsgd_capturable_begin(r.t)
+                for _ in range(int(rng.integers(1, 4))):
+                    t = r.t
+                    r.make_gradients()
+                    _, synced = r.ora.iteration(t, r.alpha, r.eta)
+                    r.lib.palsgd_step_capturable(ae)
+                    if synced:
+                        r.lib.palsgd_outer_step(t)
+                    r.t += 1
+                assert r.lib.palsgd_capturable_end() == r.t
+            torch.cuda.synchronize()
+            if op in ("step", "sync_fused", "split", "clip_step", "diagnostics", "outer_now", "outer_diag_now", "capturable",
+                      "finish"):
+                shared = False                                  # each of these gives every worker its own rows first
+            if not shared:
+                r.compare()
+        except Exception:
+            print("sequence so far:", log)
+            raise
+    r.lib.palsgd_ddp_finish()                                   # rows that a warm-up left shared, if the sequence ended in one
+    try:
+        r.compare()
+    except AssertionError:
+        print("sequence:", log)
+        raise
+    r.close()
