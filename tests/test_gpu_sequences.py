@@ -41,7 +41,8 @@ def test_random_call_sequence(seed):
     shared = False        # a DDP warm-up keeps the InnerOPT state (and with ddp_shared the model) once, until a later call needs the rows
     for _ in range(40):
         op = str(rng.choice(["step", "step", "step", "sync_fused", "split", "ddp", "ddp_shared", "clip_step", "clip_ddp",
-                             "diagnostics", "outer_now", "outer_diag_now", "state", "capturable", "finish", "outer_lr"]))
+                             "diagnostics", "outer_now", "outer_diag_now", "state", "capturable", "finish", "outer_lr",
+                             "tuning", "scaled_step", "forced_step"]))
         log.append(op)
         try:
             if op == "step":
@@ -50,6 +51,14 @@ def test_random_call_sequence(seed):
                 r.iterate(int(rng.integers(1, 4)), fused_sync=True)
             elif op == "split":                                 # the two branches as separate calls
                 r.iterate(1, fused=False)
+            elif op == "scaled_step":                           # caller-side gradient multipliers
+                r.iterate(1, grad_scale=list(rng.uniform(0.25, 2.0, K)), fused_sync=bool(rng.integers(2)))
+            elif op == "forced_step":                           # branches given by the caller instead of the draws
+                mask = [int(v) for v in rng.integers(0, 2, K)]
+                r.iterate(1, mask_fn=lambda t: mask, fused=bool(rng.integers(2)))
+            elif op == "tuning":                                # launch shapes: results may differ in the K-sum order only
+                r.lib.palsgd_set_tuning(int(rng.choice([0, 3, 8, 32])), int(rng.choice([0, 3, 4, 32])),
+                                        int(rng.choice([0, 1, 2])))
             elif op in ("ddp", "ddp_shared", "clip_ddp"):
                 if not _identical_step_counts(r):               # the DDP step needs identical workers: refused, nothing changes
                     with pytest.raises(PalsgdError) as e:
@@ -57,7 +66,8 @@ def test_random_call_sequence(seed):
                     assert e.value.status == 4
                 else:
                     r.ddp_iterate(int(rng.integers(1, 3)), shared=op == "ddp_shared",
-                                  clip=0.5 if op == "clip_ddp" else None)
+                                  clip=0.5 if op == "clip_ddp" else None,
+                                  grad_scale=list(rng.uniform(0.5, 1.5, K)) if rng.integers(2) else None)
                     shared = True
             elif op == "clip_step":
                 r.iterate(1, clip=0.5)
@@ -97,7 +107,7 @@ def test_random_call_sequence(seed):
                 assert r.lib.palsgd_capturable_end() == r.t
             torch.cuda.synchronize()
             if op in ("step", "sync_fused", "split", "clip_step", "diagnostics", "outer_now", "outer_diag_now", "capturable",
-                      "finish"):
+                      "finish", "scaled_step", "forced_step"):
                 shared = False                                  # each of these gives every worker its own rows first
             if not shared:
                 r.compare()
