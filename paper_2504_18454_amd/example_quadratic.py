@@ -34,17 +34,19 @@ def run(K=8, numels=(50000, 1000, 64), warmup=20, steps=200, H=10, p=0.1, alpha=
     diag = torch.zeros(2, dtype=f, device=dev)
     history = []
 
-    def gradients():
-        torch.sub(X, c, out=G)
+    def gradients(model):
+        torch.sub(model, c, out=G) if model.dim() == 2 else G.copy_((model - c).expand_as(G))
         G.add_(torch.randn(G.shape, dtype=f, device=dev, generator=gen), alpha=sigma)
         G.mul_(real)
 
     for t in range(warmup):                       # DDP warm-up: every worker applies the averaged gradient
-        gradients()
+        gradients(XG)                             # one common model during the warm-up: XG (the rows of X follow later)
         opt.palsgd_clip_mean_grad_norm(clip)      # DDP clips the averaged gradient
-        opt.palsgd_ddp_step(t, alpha)
+        opt.palsgd_ddp_step_shared(t, alpha)
     for t in range(steps):                        # PALSGD phase, t counted from 0 again
-        gradients()
+        if t == 0:
+            opt.palsgd_ddp_finish()               # every worker gets its model row and InnerOPT state
+        gradients(X)
         opt.palsgd_clip_grad_norm(clip)
         opt.palsgd_step(t, alpha, eta)
         if (t + 1) % H == 0:
