@@ -32,6 +32,9 @@ def _load():
                                   C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
         _lib.ora_outer.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p,
                                    C.c_uint64, C.c_double, C.c_double, C.c_int]
+        _lib.ora_outer_adamw.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_uint64, C.c_double, C.c_double, C.c_double, C.c_double, C.c_double,
+                                         C.c_uint64]
         _lib.ora_local_step.argtypes = [C.c_void_p, C.c_uint64, C.c_double, C.c_double,
                                         C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.ora_outer_step.argtypes = [C.c_void_p]
@@ -103,6 +106,14 @@ def outer(X, xg, om, lr_o, mu_o, nesterov):
                       xg.size, float(lr_o), float(mu_o), int(bool(nesterov)))
 
 
+def outer_adamw(X, xg, om, ov, lr_o, beta1, beta2, eps, wd, step):
+    """Outer step with OuterOPT = AdamW; `step` counts outer steps from 1.  X, xg, om, ov updated in place."""
+    K, row = X.shape
+    _load().ora_outer_adamw(_ptr(X, np.float32), row, K, _ptr(xg, np.float32), _ptr(om, np.float32),
+                            _ptr(ov, np.float32), xg.size, float(lr_o), float(beta1), float(beta2), float(eps),
+                            float(wd), int(step))
+
+
 def grad_norm(g):
     gp, gd = _gptr(g)
     return float(_load().ora_grad_norm(gp, gd, g.size))
@@ -143,6 +154,8 @@ class _CState(C.Structure):
         ("outer_nesterov", C.c_int), ("seed", C.c_uint64),
         ("X", C.c_void_p), ("M", C.c_void_p), ("V", C.c_void_p), ("G", C.c_void_p),
         ("XG", C.c_void_p), ("OM", C.c_void_p), ("tau", C.c_void_p), ("n_outer", C.c_uint64),
+        ("outer_opt", C.c_int), ("outer_beta1", C.c_double), ("outer_beta2", C.c_double),
+        ("outer_eps", C.c_double), ("outer_weight_decay", C.c_double), ("OV", C.c_void_p),
     ]
 
 
@@ -158,7 +171,8 @@ class OracleState:
     def __init__(self, K, x0, tensor_offset, tensor_numel, *, inner="adamw", grad_dtype="f32",
                  beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, momentum=0.9, p=0.1, H=16,
                  outer_lr=0.2, outer_momentum=0.9, outer_nesterov=True, seed=0, wd_mult=None,
-                 inner_nesterov=False):
+                 inner_nesterov=False, outer_opt="sgd", outer_beta1=0.9, outer_beta2=0.999, outer_eps=1e-8,
+                 outer_weight_decay=0.0):
         self.lib = _load()
         x0 = np.ascontiguousarray(x0, dtype=np.float32)
         row = x0.size
@@ -195,6 +209,11 @@ class OracleState:
         s.G, s.XG, s.OM = self.G.ctypes.data, self.XG.ctypes.data, self.OM.ctypes.data
         s.tau = self.tau.ctypes.data
         s.n_outer = 0
+        self.OV = np.zeros(row, np.float32)
+        s.outer_opt = 0 if outer_opt == "sgd" else 1
+        s.outer_beta1, s.outer_beta2, s.outer_eps = f32(outer_beta1), f32(outer_beta2), f32(outer_eps)
+        s.outer_weight_decay = f32(outer_weight_decay)
+        s.OV = self.OV.ctypes.data
         self.s = s
 
     def set_outer_lr(self, outer_lr):

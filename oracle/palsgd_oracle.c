@@ -208,6 +208,39 @@ void ora_outer(float *X, uint64_t row_stride, uint32_t K, float *xg, float *om,
 }
 
 /* ------------------------------------------------------------------------- */
+/* Outer step with OuterOPT = AdamW, one of the optimizer pairs that App. C   */
+/* compares (Alg. 1 leaves OuterOPT open): Delta as above plays the gradient, */
+/* om and ov are the two moments, step = number of this outer step (from 1):  */
+/*   om <- b1 om + (1-b1) Delta        ov <- b2 ov + (1-b2) Delta^2           */
+/*   x  <- x - lr_o ( (om/(1-b1^step)) / (sqrt(ov/(1-b2^step)) + eps) + wd x )*/
+/* then every worker restarts from x.                                         */
+/* ------------------------------------------------------------------------- */
+void ora_outer_adamw(float *X, uint64_t row_stride, uint32_t K, float *xg, float *om,
+                     float *ov, uint64_t n, double lr_o, double b1, double b2, double eps,
+                     double wd, uint64_t step)
+{
+    const double bc1 = 1.0 - pow(b1, (double)step);
+    const double bc2 = 1.0 - pow(b2, (double)step);
+    int64_t i;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (i = 0; i < (int64_t)n; ++i) {
+        double sum = 0.0;
+        for (uint32_t k = 0; k < K; ++k)
+            sum += (double)X[(uint64_t)k * row_stride + (uint64_t)i];
+        double xi = (double)xg[i];
+        double delta = xi - sum / (double)K;
+        double m = b1 * (double)om[i] + (1.0 - b1) * delta;
+        double v = b2 * (double)ov[i] + (1.0 - b2) * delta * delta;
+        float xnew = (float)(xi - lr_o * ((m / bc1) / (sqrt(v / bc2) + eps) + wd * xi));
+        om[i] = (float)m;
+        ov[i] = (float)v;
+        xg[i] = xnew;
+        for (uint32_t k = 0; k < K; ++k)
+            X[(uint64_t)k * row_stride + (uint64_t)i] = xnew;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* Whole-algorithm driver: one iteration t of the inner loop of Alg. 1 for    */
 /* all K workers, in the order the listing gives: draw, local update (mix or  */
 /* gradient step), then the (t+1) mod H test and the outer step.              */
@@ -237,6 +270,10 @@ typedef struct {
     float *XG, *OM;          /* [row_stride]                                  */
     uint64_t *tau;           /* [K] gradient steps taken per replica          */
     uint64_t n_outer;        /* outer steps taken                             */
+    /* OuterOPT = AdamW instead of the SGD family (outer_opt != 0)             */
+    int outer_opt;
+    double outer_beta1, outer_beta2, outer_eps, outer_weight_decay;
+    float *OV;               /* [row_stride] second moment of the outer AdamW */
 } ora_state;
 
 /* Local update of step t for every replica.  mask_out (nullable) receives    */
@@ -288,8 +325,13 @@ void ora_local_step(ora_state *s, uint64_t t, double alpha_t, double eta_t,
 
 void ora_outer_step(ora_state *s)
 {
-    ora_outer(s->X, s->row_stride, s->K, s->XG, s->OM, s->n, s->outer_lr,
-              s->outer_momentum, s->outer_nesterov);
+    if (s->outer_opt)
+        ora_outer_adamw(s->X, s->row_stride, s->K, s->XG, s->OM, s->OV, s->n, s->outer_lr,
+                        s->outer_beta1, s->outer_beta2, s->outer_eps, s->outer_weight_decay,
+                        s->n_outer + 1);
+    else
+        ora_outer(s->X, s->row_stride, s->K, s->XG, s->OM, s->n, s->outer_lr,
+                  s->outer_momentum, s->outer_nesterov);
     s->n_outer += 1;
 }
 

@@ -53,6 +53,8 @@ class BruteForce:
         self.v = [[0.0] * len(x0) for _ in range(K)]
         self.xg = [float(v) for v in x0]
         self.om = [0.0] * len(x0)
+        self.ov = [0.0] * len(x0)
+        self.outer_count = 0
         self.tau = [0] * K
 
     @staticmethod
@@ -100,32 +102,46 @@ class BruteForce:
         if (t + 1) % hp["H"] == 0:
             for i in range(len(self.xg)):
                 delta = sum(self.xg[i] - self.x[k][i] for k in range(self.K)) / self.K
+                if hp.get("outer_adamw"):                   # OuterOPT = AdamW on Delta, 'decay first' form
+                    n = self.outer_count + 1
+                    m = hp["ob1"] * self.om[i] + (1 - hp["ob1"]) * delta
+                    v = hp["ob2"] * self.ov[i] + (1 - hp["ob2"]) * delta * delta
+                    denom = v ** 0.5 / (1 - hp["ob2"] ** n) ** 0.5 + hp["oeps"]
+                    x = self.xg[i] * (1 - hp["lr_o"] * hp["owd"]) - hp["lr_o"] / (1 - hp["ob1"] ** n) * m / denom
+                    self.xg[i], self.om[i], self.ov[i] = self.r(x), self.r(m), self.r(v)
+                    for k in range(self.K):
+                        self.x[k][i] = self.xg[i]
+                    continue
                 om = hp["mu_o"] * self.om[i] + delta
                 d = delta + hp["mu_o"] * om if hp["nesterov"] else om
                 self.xg[i] = self.r(self.xg[i] - hp["lr_o"] * d)
                 self.om[i] = self.r(om)
                 for k in range(self.K):
                     self.x[k][i] = self.xg[i]
+            self.outer_count += 1
 
 
 @pytest.mark.parametrize("K,H,numels,inner,nesterov", [
     (1, 1, [1], "adamw", True), (2, 2, [1], "sgdm", True), (2, 3, [3], "adamw", False),
     (3, 2, [5, 17], "adamw", True), (3, 3, [17, 1, 3], "sgdm", False), (2, 1, [5], "sgdm", True),
-    (3, 2, [3, 5], "sgdm_nesterov", True),
+    (3, 2, [3, 5], "sgdm_nesterov", True), (3, 2, [5, 3], "adamw_outeradamw", True), (2, 3, [3], "sgdm_outeradamw", True),
 ])
 def test_brute_force_tiny(oracle_mod, K, H, numels, inner, nesterov):
     inner_nesterov = inner.endswith("_nesterov")
+    outer_adamw = inner.endswith("_outeradamw")
     inner = inner.split("_")[0]
     rng = np.random.default_rng(100 + K * 7 + H)
     offs, row = flat_layout(numels)
     x0 = _padded(rng, numels)
     wdm = [1.0, 0.0, 2.0][:len(numels)]
     hp = dict(p=0.3, H=H, b1=F(0.9), b2=F(0.999), eps=F(1e-8), wd=F(0.05), mu=F(0.8),
-              lr_o=F(0.7), mu_o=F(0.9), nesterov=nesterov, inner_nesterov=inner_nesterov)
+              lr_o=F(0.7), mu_o=F(0.9), nesterov=nesterov, inner_nesterov=inner_nesterov,
+              outer_adamw=outer_adamw, ob1=F(0.8), ob2=F(0.95), oeps=F(1e-6), owd=F(0.1))
     seed = 99
     st = _state(oracle_mod, K, x0, numels, inner=inner, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.05,
                 momentum=0.8, p=0.3, H=H, outer_lr=0.7, outer_momentum=0.9, outer_nesterov=nesterov,
-                seed=seed, wd_mult=wdm, inner_nesterov=inner_nesterov)
+                seed=seed, wd_mult=wdm, inner_nesterov=inner_nesterov, outer_opt="adamw" if outer_adamw else "sgd",
+                outer_beta1=0.8, outer_beta2=0.95, outer_eps=1e-6, outer_weight_decay=0.1)
     bf = BruteForce(K, x0, numels, wdm, inner, hp, seed)
     alpha, eta = F(0.01), F(4.0)
     mixed = 0
@@ -139,7 +155,7 @@ def test_brute_force_tiny(oracle_mod, K, H, numels, inner, nesterov):
         mixed += int(mask.sum())
         assert synced == ((t + 1) % H == 0)
         for name, got, want in (("X", st.X, bf.x), ("M", st.M, bf.m), ("XG", st.XG[None], [bf.xg]),
-                                ("OM", st.OM[None], [bf.om])):
+                                ("OM", st.OM[None], [bf.om]), ("OV", st.OV[None], [bf.ov])):
             np.testing.assert_allclose(got, np.array(want), rtol=3e-7, atol=1e-9, err_msg=f"{name} t={t}")
         if inner == "adamw":
             np.testing.assert_allclose(st.V, np.array(bf.v), rtol=3e-7, atol=1e-12)

@@ -273,6 +273,49 @@ def test_outer_matches_library_sgd_fed_delta(oracle_mod, nesterov):
         assert all(np.array_equal(X[k], xg) or _ulp_diff(X[k], xg).max() <= 1 for k in range(K))
 
 
+@pytest.mark.parametrize("wd", [0.0, float(f32(0.05))])
+def test_outer_adamw_matches_library_fed_delta(oracle_mod, wd):
+    # OuterOPT = AdamW (App. C compares it with the SGD family): the library optimizer, in float64, with Delta as
+    # its gradient and fp32 rounding of the stored state between outer steps
+    rng = np.random.default_rng(12)
+    K, n, lr_o = 4, 2048, float(f32(0.01))
+    xg = rng.standard_normal(n).astype(f32); om = np.zeros(n, f32); ov = np.zeros(n, f32)
+    p = torch.nn.Parameter(torch.tensor(xg, dtype=torch.float64))
+    opt = torch.optim.AdamW([p], lr=lr_o, betas=(B1, B2), eps=EPS, weight_decay=wd)
+    for it in range(6):
+        X = (xg[None, :] + 0.01 * rng.standard_normal((K, n))).astype(f32)
+        p.grad = p.detach() - torch.tensor(X, dtype=torch.float64).mean(dim=0)
+        opt.step()
+        oracle_mod.outer_adamw(X, xg, om, ov, lr_o, B1, B2, EPS, wd, it + 1)
+        _near_bit_exact(xg, p.detach().numpy())
+        st = opt.state[p]
+        _near_bit_exact(om, st["exp_avg"].numpy())
+        _near_bit_exact(ov, st["exp_avg_sq"].numpy())
+        with torch.no_grad():
+            p.copy_(p.float().double())
+            st["exp_avg"].copy_(st["exp_avg"].float().double())
+            st["exp_avg_sq"].copy_(st["exp_avg_sq"].float().double())
+        xg = p.detach().numpy().astype(f32)
+        om = st["exp_avg"].numpy().astype(f32); ov = st["exp_avg_sq"].numpy().astype(f32)
+        assert all(np.array_equal(X[k], xg) or _ulp_diff(X[k], xg).max() <= 1 for k in range(K))
+
+
+def test_outer_adamw_first_step_is_a_sign_step(oracle_mod):
+    # from zero moments the bias-corrected ratio is Delta/|Delta|: x1 = x0 - lr (sign(Delta)/(1 + eps/|Delta|) + wd x0)
+    K, n, lr_o, wd = 3, 6, 0.125, 0.5
+    xg = np.array([1.0, -2.0, 0.5, 4.0, -1.0, 0.0], f32)
+    X = np.stack([xg - f32(0.5), xg - f32(0.25), xg - f32(0.75)]).astype(f32)       # Delta = +0.5 everywhere
+    X[:, 3:] = xg[3:] + f32(0.5)                                                     # ... and -0.5 in the second half
+    om = np.zeros(n, f32); ov = np.zeros(n, f32)
+    x0 = xg.astype(np.float64)
+    oracle_mod.outer_adamw(X, xg, om, ov, lr_o, 0.5, 0.75, 0.0, wd, 1)
+    sign = np.array([1, 1, 1, -1, -1, -1], np.float64)
+    np.testing.assert_array_equal(xg, (x0 - lr_o * (sign + wd * x0)).astype(f32))
+    np.testing.assert_array_equal(om, (0.5 * 0.5 * sign).astype(f32))               # (1 - b1) Delta
+    np.testing.assert_array_equal(ov, np.full(n, 0.25 * 0.25, f32))                 # (1 - b2) Delta^2
+    assert all(np.array_equal(X[k], xg) for k in range(K))
+
+
 def test_outer_sum_runs_over_all_replicas_with_stride(oracle_mod):
     # brute force on integers (exact in floating point): catches a wrong stride or a skipped k
     K, n, row = 7, 5, 11
