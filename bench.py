@@ -73,7 +73,7 @@ def grad_bytes_per_elem(inner: str, grad_dtype: str) -> int:
 
 
 def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=False, graph=False, wd_mult=None,
-            fused_sync=False):
+            fused_sync=False, outer_adamw=False):
     import torch
 
     from paper_2504_18454_amd import Palsgd, make_config, palsgd_layout
@@ -82,7 +82,8 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     binding.lib()                                       # fail loudly if the HIP library is missing
     dev = torch.device("cuda:0")
     cfg = make_config(w.K, w.numels, inner=w.inner, grad_dtype=w.grad_dtype, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
-                      weight_decay=w.weight_decay, momentum=w.momentum, p=w.p, H=w.H, outer_lr=w.outer_lr,
+                      weight_decay=w.weight_decay, momentum=w.momentum, p=w.p, H=w.H,
+                      outer_lr=1e-3 if outer_adamw else w.outer_lr, outer_opt="adamw" if outer_adamw else "sgd",
                       outer_momentum=w.outer_momentum, outer_nesterov=w.outer_nesterov, seed=w.seed, wd_mult=wd_mult)
     row, offs = palsgd_layout(cfg)
     K = w.K
@@ -118,7 +119,8 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     torch.cuda.synchronize()
     del cal_src, cal_dst
     stream = torch.cuda.Stream(device=dev)
-    ctx = Palsgd(cfg, X, M, V, G, XG, OM, row, x0=x0, stream=stream)
+    OV = torch.empty(row, dtype=f, device=dev) if outer_adamw else None   # second moment of OuterOPT = AdamW
+    ctx = Palsgd(cfg, X, M, V, G, XG, OM, row, x0=x0, stream=stream, OV=OV)
     if step_waves or outer_waves or outer_variant:
         ctx.palsgd_set_tuning(step_waves, outer_waves, outer_variant)
     torch.cuda.synchronize()
@@ -162,7 +164,7 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     plain = [i for i in range(steps) if not (fused_sync and synced[i])]      # launches of step_kernel
     step_ms, step_bytes = [all_ms[i] for i in plain], [all_bytes[i] for i in plain]
     outer_ms = [events[i][1].elapsed_time(events[i][2]) for i in range(steps) if synced[i]]
-    outer_bytes = float(P) * (8 * K + 16)
+    outer_bytes = float(P) * (8 * K + 16 + (8 if outer_adamw else 0))
     total_bytes = sum(all_bytes) + outer_bytes * len(outer_ms)
     fused_ms = [all_ms[i] for i in range(steps) if fused_sync and synced[i]]
     res = dict(
@@ -289,6 +291,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decay-1d", action="store_true",
                     help="weight-decay multiplier 0 on one-dimensional tensors (biases, norms): exercises the per-tensor table")
+    ap.add_argument("--outer-adamw", action="store_true",
+                    help="OuterOPT = AdamW (outer lr 1e-3) instead of the workload's Nesterov momentum")
     ap.add_argument("--fused-sync", action="store_true",
                     help="synchronisation steps as ONE launch (palsgd_step_sync) instead of palsgd_step + palsgd_outer_step")
     ap.add_argument("--graph", action="store_true",
@@ -303,7 +307,7 @@ def main():
     from paper_2504_18454_amd.workloads import workload
     w = workload(a.workload)
     wd_mult = [0.0 if len(shape) == 1 else 1.0 for _, shape in w.tensors] if a.no_decay_1d else None
-    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph, wd_mult, a.fused_sync)
+    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph, wd_mult, a.fused_sync, a.outer_adamw)
     cpu = None
     if not a.no_cpu_baseline:
         cpu = run_cpu_baseline(w)
@@ -317,7 +321,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": a.workload, "K": w.K, "P": w.P, "tensors": len(w.tensors), "inner": w.inner,
                    "grad_dtype": w.grad_dtype, "p": w.p, "H": w.H, "eta": w.eta, "alpha": w.alpha,
-                   "outer": f"nesterov lr {w.outer_lr} mu {w.outer_momentum}", "outer_steps_timed": r["n_outer"],
+                   "outer": "adamw lr 0.001" if a.outer_adamw else f"nesterov lr {w.outer_lr} mu {w.outer_momentum}", "outer_steps_timed": r["n_outer"],
                    "mix_fraction_timed": round(r["mix_fraction"], 4),
                    "weight_decay": "uniform" if not a.no_decay_1d else "per tensor: 0 on 1-D tensors"},
         "hbm_GBps_whole_step": r["blended_gbps"], "hbm_frac_whole_step": r["blended_gbps"] / HBM_PEAK_GBPS,
@@ -328,7 +332,7 @@ def main():
                      "bytes_per_elem": {"grad": gb, "mix": 12}},
         "outer_kernel": {"ms_per_launch": r["outer_kernel_ms"], "achieved": r["outer_kernel_gbps"], "unit": "GB/s",
                          "frac": (r["outer_kernel_gbps"] / HBM_PEAK_GBPS) if r["outer_kernel_gbps"] else None,
-                         "bytes_per_elem": 8 * w.K + 16},
+                         "bytes_per_elem": 8 * w.K + 16 + (8 if a.outer_adamw else 0)},
         "cpu_baseline": cpu,
     }
     if a.fused_sync:

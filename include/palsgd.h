@@ -58,6 +58,7 @@ typedef enum {
 
 typedef enum { PALSGD_INNER_ADAMW = 0, PALSGD_INNER_SGDM = 1 } palsgd_inner_opt;
 typedef enum { PALSGD_GRAD_F32 = 0, PALSGD_GRAD_BF16 = 1 } palsgd_grad_dtype;
+typedef enum { PALSGD_OUTER_SGD = 0, PALSGD_OUTER_ADAMW = 1 } palsgd_outer_opt;
 
 /* Inputs of Algorithm 1 plus the constants of the two optimizers (Sec. 4.3). */
 typedef struct {
@@ -80,13 +81,18 @@ typedef struct {
     float outer_momentum;         /* OuterOPT momentum, 0 = plain SGD                       */
     int32_t outer_nesterov;       /* 1: Nesterov momentum (Sec. 4.3), 0: heavy ball         */
     uint64_t seed;                /* seed of the branch draws                               */
+    int32_t outer_opt;            /* palsgd_outer_opt: SGD family above (Sec. 4.3), or AdamW
+                                     with Delta as its gradient (the optimizer pairs of App. C) */
+    float outer_beta1, outer_beta2, outer_eps; /* OuterOPT = AdamW: moments and epsilon     */
+    float outer_weight_decay;     /* OuterOPT = AdamW: decoupled weight decay               */
 } palsgd_config;
 
 typedef struct {
     float *X, *M, *V; /* device */
     void *G;          /* device, float or bf16 according to grad_dtype */
-    float *XG, *OM;   /* device */
+    float *XG, *OM;   /* device; OM: OuterOPT momentum buffer, or first moment with AdamW */
     uint64_t row_stride;
+    float *OV;        /* device [row_stride]: second moment of OuterOPT = AdamW, else NULL */
 } palsgd_buffers;
 
 /* Flat layout of a row: tensor_offset[j] (host array [n_tensors], may be NULL) is the
@@ -145,7 +151,12 @@ palsgd_status palsgd_step_sync(palsgd_ctx *ctx, uint64_t t, float alpha_t, float
 /* Outer step (Alg. 1, the two lines of the synchronisation branch; Sec. 4.2):
  * Delta = XG - (1/K) sum_k X[k];  OM <- mu OM + Delta;
  * XG <- XG - outer_lr (Delta + mu OM) (Nesterov) or XG - outer_lr OM;  X[k] <- XG for
- * all k (Sec. 2.1: workers restart from the global model).  The caller decides when
+ * all k (Sec. 2.1: workers restart from the global model).  With outer_opt = AdamW:
+ * OM <- b1 OM + (1-b1) Delta, OV <- b2 OV + (1-b2) Delta^2,
+ * XG <- XG - outer_lr ((OM/(1-b1^n)) / (sqrt(OV/(1-b2^n)) + eps) + wd XG), n = number of
+ * this outer step (from 1; part of palsgd_get_state / palsgd_set_state).  The bias
+ * corrections are launch arguments computed from n on the host, so an outer step with
+ * AdamW that was captured into a HIP graph must not be replayed.  The caller decides when
  * ((t+1) mod H == 0 in Alg. 1); t is recorded for diagnostics only. */
 palsgd_status palsgd_outer_step(palsgd_ctx *ctx, uint64_t t, void *stream);
 

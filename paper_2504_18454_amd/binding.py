@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libpalsgd.so")
 PALSGD_OK, PALSGD_EINVAL, PALSGD_ENOMEM, PALSGD_EHIP, PALSGD_ESTATE = range(5)
 INNER = {"adamw": 0, "sgdm": 1}
 GRAD = {"f32": 0, "bf16": 1}
+OUTER = {"sgd": 0, "adamw": 1}
 MAX_K = 64
 
 EXPORTS = ("palsgd_layout", "palsgd_init", "palsgd_draw", "palsgd_inner_step", "palsgd_pseudo_sync",
@@ -44,12 +45,14 @@ class Config(C.Structure):
                 ("weight_decay", C.c_float), ("momentum", C.c_float), ("inner_nesterov", C.c_int32),
                 ("p", C.c_double), ("H", C.c_uint32),
                 ("outer_lr", C.c_float), ("outer_momentum", C.c_float), ("outer_nesterov", C.c_int32),
-                ("seed", C.c_uint64)]
+                ("seed", C.c_uint64), ("outer_opt", C.c_int32),
+                ("outer_beta1", C.c_float), ("outer_beta2", C.c_float), ("outer_eps", C.c_float),
+                ("outer_weight_decay", C.c_float)]
 
 
 class Buffers(C.Structure):
     _fields_ = [("X", C.c_void_p), ("M", C.c_void_p), ("V", C.c_void_p), ("G", C.c_void_p),
-                ("XG", C.c_void_p), ("OM", C.c_void_p), ("row_stride", C.c_uint64)]
+                ("XG", C.c_void_p), ("OM", C.c_void_p), ("row_stride", C.c_uint64), ("OV", C.c_void_p)]
 
 
 _lib = None
@@ -120,7 +123,9 @@ def make_config(K: int, tensor_numel: Sequence[int], *, inner: str = "adamw", gr
                 beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.01,
                 momentum: float = 0.9, p: float = 0.1, H: int = 16, outer_lr: float = 0.2,
                 outer_momentum: float = 0.9, outer_nesterov: bool = True, seed: int = 0,
-                wd_mult: Optional[Sequence[float]] = None, inner_nesterov: bool = False) -> Config:
+                wd_mult: Optional[Sequence[float]] = None, inner_nesterov: bool = False,
+                outer_opt: str = "sgd", outer_beta1: float = 0.9, outer_beta2: float = 0.999,
+                outer_eps: float = 1e-8, outer_weight_decay: float = 0.0) -> Config:
     cfg = Config()
     n = len(tensor_numel)
     numel = (C.c_uint64 * max(n, 1))(*[int(v) for v in tensor_numel])
@@ -139,6 +144,9 @@ def make_config(K: int, tensor_numel: Sequence[int], *, inner: str = "adamw", gr
     cfg.p, cfg.H = float(p), int(H)
     cfg.outer_lr, cfg.outer_momentum, cfg.outer_nesterov = outer_lr, outer_momentum, int(bool(outer_nesterov))
     cfg.seed = int(seed) & (2 ** 64 - 1)
+    cfg.outer_opt = OUTER[outer_opt] if isinstance(outer_opt, str) else int(outer_opt)
+    cfg.outer_beta1, cfg.outer_beta2, cfg.outer_eps = outer_beta1, outer_beta2, outer_eps
+    cfg.outer_weight_decay = outer_weight_decay
     return cfg
 
 
@@ -182,16 +190,16 @@ def _stream_handle(stream) -> Optional[int]:
 class Palsgd:
     """A context over caller-owned device buffers; one method per C entry point.
 
-    X, M, V, G, XG, OM are torch CUDA tensors (V may be None for SGD-momentum) or raw
-    device addresses; they must outlive the context.
+    X, M, V, G, XG, OM (and OV with OuterOPT = AdamW) are torch CUDA tensors (V may be None
+    for SGD-momentum) or raw device addresses; they must outlive the context.
     """
 
-    def __init__(self, cfg: Config, X, M, V, G, XG, OM, row_stride: int, x0=None, stream=None):
+    def __init__(self, cfg: Config, X, M, V, G, XG, OM, row_stride: int, x0=None, stream=None, OV=None):
         ptr = lambda t: None if t is None else (t if isinstance(t, int) else t.data_ptr())
-        self._tensors = (X, M, V, G, XG, OM, x0)          # keep references
+        self._tensors = (X, M, V, G, XG, OM, OV, x0)      # keep references
         self.cfg = cfg
         self.K = int(cfg.K)
-        buf = Buffers(ptr(X), ptr(M), ptr(V), ptr(G), ptr(XG), ptr(OM), int(row_stride))
+        buf = Buffers(ptr(X), ptr(M), ptr(V), ptr(G), ptr(XG), ptr(OM), int(row_stride), ptr(OV))
         out = C.c_void_p()
         st = lib().palsgd_init(C.byref(cfg), C.byref(buf), ptr(x0), _stream_handle(stream), C.byref(out))
         _check(st, None)

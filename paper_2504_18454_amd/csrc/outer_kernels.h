@@ -10,13 +10,23 @@ namespace palsgd_dev {
 struct OuterArgs {
     float inv_k, lr, mu;
     int nesterov;
+    // OuterOPT = AdamW with Delta as its gradient, instead of the SGD family:
+    float b1, b2, eps;     // its decay rates and epsilon
+    float c1, c2, decay;   // for this outer step n: lr/(1-b1^n), 1/sqrt(1-b2^n), lr*wd
 };
 
 // OuterOPT on four elements given dsum = sum_k (x - x_k) (Sec. 4.2; Sec. 4.3).  Summing the
 // differences instead of the models keeps Delta accurate to fp32 relative to its own size
-// and makes it exactly zero when the workers equal the global model.
-__device__ __forceinline__ f4 outer4(f4 dsum, f4 xg, f4& om, const OuterArgs& a) {
+// and makes it exactly zero when the workers equal the global model.  om is the momentum
+// buffer of the SGD family or the first moment of AdamW; ov (AdamW only) the second moment.
+template <bool OADAM>
+__device__ __forceinline__ f4 outer4(f4 dsum, f4 xg, f4& om, f4& ov, const OuterArgs& a) {
     f4 delta = dsum * a.inv_k;                     // Delta = mean_k (x - x_k)
+    if (OADAM) {
+        const Hyper h{a.b1, a.b2, a.eps, 0.f, 0.f, 0};
+        adamw4(xg, om, ov, delta, h, a.c1, a.c2, a.decay);
+        return xg;
+    }
     om = a.mu * om + delta;
     f4 dir = a.nesterov ? delta + a.mu * om : om;
     return xg - a.lr * dir;
@@ -26,9 +36,11 @@ __device__ __forceinline__ f4 outer4(f4 dsum, f4 xg, f4& om, const OuterArgs& a)
 // K rows in ascending order, eight independent loads in flight at a time.
 // DIAG: also leaves, per wavefront, the partial sums of sum_k |x - x_k|^2 and |Delta|^2
 // (App. A.3) taken from the values already in registers: no extra HBM reads.
-template <bool DIAG>
+// OADAM: OuterOPT = AdamW (a compile-time switch: as a run-time one it slowed the SGD-family
+// outer step by a quarter).
+template <bool DIAG, bool OADAM>
 __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X, float* __restrict__ XG,
-                                                           float* __restrict__ OM, uint64_t n,
+                                                           float* __restrict__ OM, float* __restrict__ OV, uint64_t n,
                                                            uint64_t row_stride, uint32_t K, OuterArgs a,
                                                            float* __restrict__ partial, uint32_t n_part) {
     const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
@@ -36,7 +48,8 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
     f4 sum = {0.f, 0.f, 0.f, 0.f}, sq = {0.f, 0.f, 0.f, 0.f};
     if (active) {
         f4 xg = ld4(XG + e);
-        f4 om = ld4(OM + e);
+        f4 om = ld4(OM + e), ov;
+        if (OADAM) ov = ld4(OV + e);
         for (uint32_t k0 = 0; k0 < K; k0 += 8) {
             f4 t[8];
 #pragma unroll
@@ -50,9 +63,10 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
                     if (DIAG) sq += d * d;
                 }
         }
-        f4 xn = outer4(sum, xg, om, a);
+        f4 xn = outer4<OADAM>(sum, xg, om, ov, a);
         st4(XG + e, xn);
         st4(OM + e, om);
+        if (OADAM) st4(OV + e, ov);
         for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
     }
     if (DIAG) {
@@ -77,18 +91,20 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
 // roundings are those of step_kernel followed by outer_kernel_walk: results are bit-identical.
 constexpr int kSyncBatch = 4;
 
-template <int INNER, int GDT, bool TAB>
+template <int INNER, int GDT, bool TAB, bool OADAM>
 __global__ __launch_bounds__(kWave) void sync_step_kernel(const StepArgs args, const float* __restrict__ wd_tab,
                                                           float* __restrict__ X, float* __restrict__ M,
                                                           float* __restrict__ V, const void* __restrict__ G,
                                                           float* __restrict__ XG, float* __restrict__ OM,
+                                                          float* __restrict__ OV,
                                                           const float* __restrict__ clip_scale, uint64_t n,
                                                           uint64_t row_stride, uint32_t K, Hyper h, OuterArgs a) {
     const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
     if (e >= n) return;
     typedef GradLoad<GDT> GL;
     const f4 xg = ld4(XG + e);
-    f4 om = ld4(OM + e);
+    f4 om = ld4(OM + e), ov;
+    if (OADAM) ov = ld4(OV + e);
     const float wd = TAB ? wd_tab[e >> 6] : h.wd;
     f4 dsum = {0.f, 0.f, 0.f, 0.f};
     for (uint32_t k0 = 0; k0 < K; k0 += kSyncBatch) {
@@ -128,9 +144,10 @@ __global__ __launch_bounds__(kWave) void sync_step_kernel(const StepArgs args, c
             }
         }
     }
-    const f4 xn = outer4(dsum, xg, om, a);
+    const f4 xn = outer4<OADAM>(dsum, xg, om, ov, a);
     st4(XG + e, xn);
     st4(OM + e, om);
+    if (OADAM) st4(OV + e, ov);
     for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
 }
 
@@ -138,8 +155,9 @@ __global__ __launch_bounds__(kWave) void sync_step_kernel(const StepArgs args, c
 // k = w, w+4, ... for the whole tile, the four partial sums per element meet in LDS,
 // and wave w finishes sub-tile w: fixed-order combine, OuterOPT, stores.  Puts 4*ceil(K/4)
 // row loads in flight per lane before the first add.
+template <bool OADAM>
 __global__ __launch_bounds__(kThreads) void outer_kernel_lds(float* __restrict__ X, float* __restrict__ XG,
-                                                             float* __restrict__ OM, uint64_t n4,
+                                                             float* __restrict__ OM, float* __restrict__ OV, uint64_t n4,
                                                              uint64_t row_stride, uint32_t K, OuterArgs a) {
     __shared__ f4 part[4][4][64];  // [wave][sub-tile][lane], 16 KiB
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -170,10 +188,12 @@ __global__ __launch_bounds__(kThreads) void outer_kernel_lds(float* __restrict__
         const uint64_t e = i * 4;
         f4 sum = ((part[0][w][lane] + part[1][w][lane]) + part[2][w][lane]) + part[3][w][lane];
         f4 xg = w == 0 ? xgt[0] : (w == 1 ? xgt[1] : (w == 2 ? xgt[2] : xgt[3]));
-        f4 om = ld4(OM + e);
-        f4 xn = outer4(sum, xg, om, a);
+        f4 om = ld4(OM + e), ov;
+        if (OADAM) ov = ld4(OV + e);
+        f4 xn = outer4<OADAM>(sum, xg, om, ov, a);
         st4(XG + e, xn);
         st4(OM + e, om);
+        if (OADAM) st4(OV + e, ov);
         for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
     }
 }
@@ -182,7 +202,8 @@ __global__ __launch_bounds__(kThreads) void outer_kernel_lds(float* __restrict__
 __global__ __launch_bounds__(kThreads) void init_kernel(const float* __restrict__ x0, float* __restrict__ X,
                                                         float* __restrict__ M, float* __restrict__ V,
                                                         float* __restrict__ XG, float* __restrict__ OM,
-                                                        uint64_t n4, uint64_t row_stride, uint32_t K) {
+                                                        float* __restrict__ OV, uint64_t n4, uint64_t row_stride,
+                                                        uint32_t K) {
     uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= n4) return;
     uint64_t e = i * 4;
@@ -190,6 +211,7 @@ __global__ __launch_bounds__(kThreads) void init_kernel(const float* __restrict_
     f4 z = {0.f, 0.f, 0.f, 0.f};
     st4(XG + e, v);
     st4(OM + e, z);
+    if (OV) st4(OV + e, z);
     for (uint32_t k = 0; k < K; ++k) {
         uint64_t r = (uint64_t)k * row_stride + e;
         st4(X + r, v);

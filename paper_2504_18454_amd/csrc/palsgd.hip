@@ -187,6 +187,25 @@ uint32_t auto_waves(uint32_t bytes_per_wave, uint32_t floor_waves = 3) {
     return w < floor_waves ? floor_waves : (w > 32 ? 32 : w);
 }
 
+// Scalars of the outer step that comes next (its number, from 1, sets AdamW's bias corrections).
+OuterArgs outer_args_of(const palsgd_ctx* c) {
+    OuterArgs a{};
+    a.inv_k = (float)(1.0 / (double)c->cfg.K);
+    a.lr = c->cfg.outer_lr;
+    a.mu = c->cfg.outer_momentum;
+    a.nesterov = c->cfg.outer_nesterov ? 1 : 0;
+    if (c->cfg.outer_opt == PALSGD_OUTER_ADAMW) {
+        const double n = (double)(c->n_outer + 1);
+        a.b1 = c->cfg.outer_beta1;
+        a.b2 = c->cfg.outer_beta2;
+        a.eps = c->cfg.outer_eps;
+        a.c1 = (float)((double)c->cfg.outer_lr / (1.0 - std::pow((double)c->cfg.outer_beta1, n)));
+        a.c2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)c->cfg.outer_beta2, n)));
+        a.decay = c->cfg.outer_lr * c->cfg.outer_weight_decay;
+    }
+    return a;
+}
+
 Hyper hyper_of(const palsgd_ctx* c) {
     return Hyper{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum, c->wd_eff0, c->cfg.inner_nesterov != 0};
 }
@@ -385,12 +404,15 @@ void launch_sync_step(palsgd_ctx* c, const StepArgs& args, const float* clip, co
     Hyper h = hyper_of(c);
     const palsgd_buffers& b = c->buf;
     const uint32_t lds = lds_cap(waves, 0);
-    if (c->wd_uniform)
-        sync_step_kernel<INNER, GDT, false><<<tile_count(c), kWave, lds, st>>>(args, nullptr, b.X, b.M, b.V, b.G, b.XG, b.OM,
-                                                                             clip, c->P_padded, b.row_stride, K, h, a);
-    else
-        sync_step_kernel<INNER, GDT, true><<<tile_count(c), kWave, lds, st>>>(args, c->d_wd_tab, b.X, b.M, b.V, b.G, b.XG,
-                                                                            b.OM, clip, c->P_padded, b.row_stride, K, h, a);
+    const bool oadam = c->cfg.outer_opt == PALSGD_OUTER_ADAMW;
+#define PALSGD_SYNC(TAB, OADAM, tab)                                                                               \
+    sync_step_kernel<INNER, GDT, TAB, OADAM><<<tile_count(c), kWave, lds, st>>>(args, tab, b.X, b.M, b.V, b.G, b.XG, b.OM, \
+                                                                               b.OV, clip, c->P_padded, b.row_stride, K, h, a)
+    if (c->wd_uniform && !oadam) PALSGD_SYNC(false, false, nullptr);
+    else if (c->wd_uniform) PALSGD_SYNC(false, true, nullptr);
+    else if (!oadam) PALSGD_SYNC(true, false, c->d_wd_tab);
+    else PALSGD_SYNC(true, true, c->d_wd_tab);
+#undef PALSGD_SYNC
 }
 
 }  // namespace
@@ -439,6 +461,15 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
     PALSGD_REQUIRE(std::isfinite(cfg->outer_lr) && cfg->outer_lr >= 0.0f, "outer_lr must be finite, >= 0");
     PALSGD_REQUIRE(std::isfinite(cfg->outer_momentum) && cfg->outer_momentum >= 0.0f && cfg->outer_momentum < 1.0f,
                    "outer_momentum must satisfy 0 <= outer_momentum < 1");
+    PALSGD_REQUIRE(cfg->outer_opt == PALSGD_OUTER_SGD || cfg->outer_opt == PALSGD_OUTER_ADAMW, "unknown outer optimizer");
+    if (cfg->outer_opt == PALSGD_OUTER_ADAMW) {
+        PALSGD_REQUIRE(cfg->outer_beta1 >= 0.0f && cfg->outer_beta1 < 1.0f, "outer_beta1 must satisfy 0 <= outer_beta1 < 1");
+        PALSGD_REQUIRE(cfg->outer_beta2 >= 0.0f && cfg->outer_beta2 < 1.0f, "outer_beta2 must satisfy 0 <= outer_beta2 < 1");
+        PALSGD_REQUIRE(std::isfinite(cfg->outer_eps) && cfg->outer_eps >= 0.0f, "outer_eps must be finite, >= 0");
+        PALSGD_REQUIRE(std::isfinite(cfg->outer_weight_decay) && cfg->outer_weight_decay >= 0.0f,
+                       "outer_weight_decay must be finite, >= 0");
+        PALSGD_REQUIRE(buf->OV != nullptr && aligned16(buf->OV), "OV buffer (16-byte aligned) is required by OuterOPT = AdamW");
+    }
     PALSGD_REQUIRE(buf->X && buf->M && buf->G && buf->XG && buf->OM, "NULL device buffer");
     PALSGD_REQUIRE(aligned16(buf->X) && aligned16(buf->M) && aligned16(buf->V) && aligned16(buf->G) &&
                        aligned16(buf->XG) && aligned16(buf->OM) && aligned16(x0_dev),
@@ -482,7 +513,8 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
         uint64_t n4 = P_padded / 4;
         uint32_t blocks = (uint32_t)((n4 + kThreads - 1) / kThreads);
         init_kernel<<<blocks, kThreads, 0, (hipStream_t)stream>>>(x0_dev, buf->X, buf->M, buf->V, buf->XG, buf->OM,
-                                                                  n4, buf->row_stride, cfg->K);
+                                                                  cfg->outer_opt == PALSGD_OUTER_ADAMW ? buf->OV : nullptr, n4,
+                                                                  buf->row_stride, cfg->K);
         rc = check_launch(c, "palsgd_init");
         if (rc != PALSGD_OK) {
             memcpy(g_error, c->error, sizeof g_error);
@@ -534,7 +566,7 @@ palsgd_status palsgd_step_sync(palsgd_ctx* ctx, uint64_t t, float alpha_t, float
     rc = end_warmup_sharing(ctx, "palsgd_step_sync", st);
     if (rc != PALSGD_OK) return rc;
     const float* clip = any_grad && ctx->clip_armed ? clip_scales(ctx) : nullptr;
-    OuterArgs a{(float)(1.0 / (double)K), ctx->cfg.outer_lr, ctx->cfg.outer_momentum, ctx->cfg.outer_nesterov ? 1 : 0};
+    const OuterArgs a = outer_args_of(ctx);
     const bool adamw = ctx->cfg.inner == PALSGD_INNER_ADAMW, bf16 = ctx->cfg.grad_dtype == PALSGD_GRAD_BF16;
     if (adamw && bf16) launch_sync_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_BF16>(ctx, args, clip, a, st);
     else if (adamw) launch_sync_step<PALSGD_INNER_ADAMW, PALSGD_GRAD_F32>(ctx, args, clip, a, st);
@@ -556,13 +588,14 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
         return PALSGD_EINVAL;
     }
     const uint32_t K = ctx->cfg.K;
-    OuterArgs a{(float)(1.0 / (double)K), ctx->cfg.outer_lr, ctx->cfg.outer_momentum, ctx->cfg.outer_nesterov ? 1 : 0};
+    const OuterArgs a = outer_args_of(ctx);
     const uint64_t n = ctx->P_padded;
     hipStream_t st = (hipStream_t)stream;
     const uint32_t variant = ctx->outer_variant ? ctx->outer_variant : 1u;
     const uint32_t waves = ctx->outer_waves ? ctx->outer_waves
                                             : auto_waves((8u * K + 16u) * kTile, 4);  // rows go 8 at a time: 4 is best from K=16 up
     const palsgd_buffers& b = ctx->buf;
+    const bool oadam = ctx->cfg.outer_opt == PALSGD_OUTER_ADAMW;
     {
         palsgd_status rc = end_warmup_sharing(ctx, who, st);  // the rows of X are read here
         if (rc != PALSGD_OK) return rc;
@@ -571,18 +604,28 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
         palsgd_status rc = ensure_scratch(ctx);
         if (rc != PALSGD_OK) return rc;
         const uint32_t tiles = tile_count(ctx);
-        outer_kernel_walk<true><<<tiles, kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, n, b.row_stride, K, a,
-                                                                        scratch_partials(ctx), tiles);
+        if (oadam)
+            outer_kernel_walk<true, true><<<tiles, kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K,
+                                                                                  a, scratch_partials(ctx), tiles);
+        else
+            outer_kernel_walk<true, false><<<tiles, kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K,
+                                                                                   a, scratch_partials(ctx), tiles);
         fold_kernel<<<dim3(kFold, 2), kThreads, 0, st>>>(scratch_partials(ctx), tiles, scratch_fold(ctx));
         diag_finish_kernel<<<1, kThreads, 0, st>>>(scratch_fold(ctx), a.inv_k, diag_out_dev);
     } else if (variant == 2) {
         const uint64_t n4 = n / 4;
         uint32_t blocks = (uint32_t)((n4 + 255) / 256);
         uint32_t groups = waves / 4 ? waves / 4 : 1;  // a workgroup of this variant is four wavefronts
-        outer_kernel_lds<<<blocks, kThreads, lds_cap(groups, 16384), st>>>(b.X, b.XG, b.OM, n4, b.row_stride, K, a);
+        if (oadam)
+            outer_kernel_lds<true><<<blocks, kThreads, lds_cap(groups, 16384), st>>>(b.X, b.XG, b.OM, b.OV, n4, b.row_stride, K, a);
+        else
+            outer_kernel_lds<false><<<blocks, kThreads, lds_cap(groups, 16384), st>>>(b.X, b.XG, b.OM, b.OV, n4, b.row_stride, K, a);
+    } else if (oadam) {
+        outer_kernel_walk<false, true><<<tile_count(ctx), kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, b.OV, n,
+                                                                                       b.row_stride, K, a, nullptr, 0);
     } else {
-        outer_kernel_walk<false><<<tile_count(ctx), kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, n, b.row_stride,
-                                                                                 K, a, nullptr, 0);
+        outer_kernel_walk<false, false><<<tile_count(ctx), kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, b.OV, n,
+                                                                                        b.row_stride, K, a, nullptr, 0);
     }
     palsgd_status rc = check_launch(ctx, who);
     if (rc != PALSGD_OK) return rc;

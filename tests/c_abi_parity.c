@@ -96,6 +96,7 @@ int main(void)
 
     /* device buffers, caller-owned */
     palsgd_buffers buf;
+    memset(&buf, 0, sizeof buf);
     float *x0_dev;
     HIP(hipMalloc((void **)&buf.X, K * rb)); HIP(hipMalloc((void **)&buf.M, K * rb)); HIP(hipMalloc((void **)&buf.V, K * rb));
     HIP(hipMalloc(&buf.G, K * rb)); HIP(hipMalloc((void **)&buf.XG, rb)); HIP(hipMalloc((void **)&buf.OM, rb));

@@ -46,7 +46,7 @@ def compact_table(idx, numels, offsets):
 class Run:
     def __init__(self, K, numels, *, inner="adamw", grad_dtype="f32", p=0.1, H=16, alpha=1e-3, eta=16.0,
                  sigma=0.01, seed=0, wd_mult=None, per_edge=None, n_random=0, row_extra=0, device="cuda:0",
-                 fill_noise=True, c_scale=1.0, **hyper):
+                 fill_noise=True, c_scale=1.0, illcond_delta=None, **hyper):
         self.K, self.numels, self.inner, self.grad_dtype = K, list(numels), inner, grad_dtype
         self.p, self.H, self.alpha, self.eta, self.sigma, self.seed = p, H, alpha, eta, sigma, seed
         self.dev = torch.device(device)
@@ -90,10 +90,11 @@ class Run:
         self.G = torch.zeros(KS, dtype=gdt, device=self.dev)
         self.XG = torch.empty(self.stride, dtype=f, device=self.dev)
         self.OM = torch.empty(self.stride, dtype=f, device=self.dev)
+        self.OV = torch.empty(self.stride, dtype=f, device=self.dev) if hyper.get("outer_opt") == "adamw" else None
         if row_extra:                      # sentinel beyond the padded row: must never be touched
-            for t_ in (self.X, self.M, self.XG, self.OM) + ((self.V,) if self.V is not None else ()):
+            for t_ in self.state_arrays():
                 t_[..., self.row:] = 777.0
-        self.lib = Palsgd(self.cfg, self.X, self.M, self.V, self.G, self.XG, self.OM, self.stride, x0=x0)
+        self.lib = Palsgd(self.cfg, self.X, self.M, self.V, self.G, self.XG, self.OM, self.stride, x0=x0, OV=self.OV)
         torch.cuda.synchronize()
         # oracle over the compact row
         coff, cnum = compact_table(self.idx, self.numels, self.offsets)
@@ -102,6 +103,16 @@ class Run:
         self.ora = oracle.OracleState(K, x0_s, coff[keep], cnum[keep], inner=inner, grad_dtype=grad_dtype, p=p, H=H,
                                       seed=seed, wd_mult=wdm, **hyper)
         self.t = 0
+        # OuterOPT = AdamW divides Delta by |Delta| + eps: where |Delta| is tiny the outer step amplifies the
+        # (tolerated) difference between the two sides' x_k by outer_lr / (|Delta| + eps).  With illcond_delta
+        # set, sampled positions whose oracle-side |Delta| falls below it at some outer step are left out of
+        # the comparison of X and XG from then on (the method is element-wise, so nothing spreads); their
+        # number is reported by compare().  M, V, OM, OV stay compared everywhere.
+        self.illcond_delta = illcond_delta
+        self.illcond = np.zeros(self.idx.size, bool)
+
+    def state_arrays(self):
+        return tuple(t for t in (self.X, self.M, self.XG, self.OM, self.V, self.OV) if t is not None)
 
     # ------------------------------------------------------------------ one iteration
     def oracle_side_gradients(self):
@@ -152,12 +163,16 @@ class Run:
                 scales = np.array([oracle.clip_scale(v, float(np.float32(clip))) for v in norms])
                 gs64 = scales if gs64 is None else gs64 * scales
                 self.last_scales = scales
-            if diag_outer:                 # oracle: local update, diagnostics, then the outer step
-                assert self.full
+            if diag_outer or self.illcond_delta is not None:   # oracle: local update, a look at the state, then the outer step
                 mask_o = self.ora.local_step(t, self.alpha, self.eta, grad_scale=gs64, mask_override=mo)
                 synced = (t + 1) % self.H == 0
                 if synced:
-                    want_diag = self.ora.diagnostics()
+                    if diag_outer:
+                        assert self.full
+                        want_diag = self.ora.diagnostics()
+                    if self.illcond_delta is not None:
+                        delta = self.ora.XG.astype(np.float64) - self.ora.X.astype(np.float64).mean(axis=0)
+                        self.illcond |= (delta != 0) & (np.abs(delta) < self.illcond_delta)
                     self.ora.outer_step()
             else:
                 mask_o, synced = self.ora.iteration(t, self.alpha, self.eta, grad_scale=gs64, mask_override=mo)
@@ -238,22 +253,27 @@ class Run:
                  ("OM", self.OM, self.ora.OM)]
         if self.V is not None:
             pairs.append(("V", self.V, self.ora.V))
+        if self.OV is not None:
+            pairs.append(("OV", self.OV, self.ora.OV))
         for name, dev_t, want in pairs:
             got = self.device_sample(dev_t)
             assert np.isfinite(got).all(), name
             err = np.abs(got.astype(np.float64) - want.astype(np.float64))
             bound = rtol * np.abs(want.astype(np.float64)) + atol
+            if name in ("X", "XG") and self.illcond.any():
+                err = np.where(self.illcond, 0.0, err)
             worst[name] = float((err / bound).max())
             bad = err > bound
             assert not bad.any(), (f"{name}: {int(bad.sum())} of {bad.size} elements outside tolerance at t={self.t}; "
                                    f"worst err/bound {worst[name]:.3g}")
         if self.stride > self.row:
-            for T in (self.X, self.M, self.XG, self.OM) + ((self.V,) if self.V is not None else ()):
+            for T in self.state_arrays():
                 assert bool((T[..., self.row:] == 777.0).all()), "wrote beyond the padded row"
         # padding stays exactly zero on the device
         if self.pad_idx.numel():
             assert not bool(self.X.index_select(1, self.pad_idx).any()), "padding of X became non-zero"
             assert not bool(self.XG.index_select(0, self.pad_idx).any()), "padding of XG became non-zero"
+        worst["left_out"] = int((self.illcond & self.real_s).sum())
         return worst
 
     def close(self):

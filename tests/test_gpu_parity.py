@@ -101,6 +101,39 @@ def test_outer_learning_rate_schedule():
     r.close()
 
 
+@pytest.mark.parametrize("regime", ["damped", "usual"])
+@pytest.mark.parametrize("inner,grad_dtype,K,variant", [("adamw", "bf16", 4, 0), ("sgdm", "f32", 7, 2), ("adamw", "f32", 16, 1)])
+def test_outer_adamw(inner, grad_dtype, K, variant, regime):
+    """OuterOPT = AdamW with Delta as its gradient (one of the optimizer pairs of App. C): separate outer
+    step, fused synchronisation step (bit-identical), fused diagnostics, step counts out and in.
+
+    AdamW moves x by outer_lr * Delta / (|Delta| + eps) (first step), so a difference d between the two sides'
+    Delta (their x_k agree to the tolerance, not to the bit) reaches x as outer_lr * d / (|Delta| + eps).
+    'damped': eps >= outer_lr, the factor is at most 1 and every element is compared.  'usual': eps = 1e-8,
+    outer_lr = 1e-3; positions whose |Delta| is below 1e-4 at some outer step (a twentieth of the usual size)
+    are left out of the comparison of X and XG, and only of those two."""
+    opt = dict(outer_lr=0.01, outer_eps=0.01) if regime == "damped" else dict(outer_lr=1e-3, outer_eps=1e-8)
+    kw = dict(K=K, numels=RAGGED, inner=inner, grad_dtype=grad_dtype, p=0.2, H=2, seed=80 + K, sigma=0.05, row_extra=1,
+              outer_opt="adamw", outer_beta1=0.8, outer_beta2=0.95, outer_weight_decay=0.1,
+              illcond_delta=None if regime == "damped" else 1e-4, **opt)
+    a, b = _run(**kw), _run(**kw)
+    a.lib.palsgd_set_tuning(0, 0, variant)
+    a.iterate(6)
+    b.iterate(6, fused_sync=True)
+    wa = a.compare(); b.compare()
+    n_real = int(a.real_s.sum())
+    assert wa["left_out"] < 0.2 * n_real, (wa["left_out"], n_real)
+    if variant != 2:                                     # variant 2 adds the K rows in another order
+        for ta, tb in ((a.X, b.X), (a.XG, b.XG), (a.OM, b.OM), (a.OV, b.OV)):
+            assert torch.equal(ta, tb)
+    tau, n_outer = a.lib.palsgd_get_state()
+    assert n_outer == 3
+    a.lib.palsgd_set_state(tau, n_outer)                 # the outer step count sets the next bias correction
+    a.iterate(4, diag_outer=True)
+    print("worst err/bound, positions left out:", a.compare())
+    a.close(); b.close()
+
+
 @pytest.mark.parametrize("nesterov,mu,lr", [(True, 0.9, 0.7), (False, 0.9, 0.7), (False, 0.0, 1.0)])
 def test_outer_variants(nesterov, mu, lr):
     r = _run(K=4, numels=[10000, 130], p=0.1, H=2, seed=16, outer_lr=lr, outer_momentum=mu, outer_nesterov=nesterov)

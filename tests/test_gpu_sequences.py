@@ -33,9 +33,12 @@ def test_random_call_sequence(seed):
     rng = np.random.default_rng(1000 + seed)
     K = int(rng.choice([1, 2, 3, 5, 8]))
     inner, grad_dtype = [("adamw", "f32"), ("adamw", "bf16"), ("sgdm", "f32"), ("sgdm", "bf16")][seed % 4]
+    outer_adamw = seed % 5 == 2
     r = _run(K=K, numels=NUMELS, inner=inner, grad_dtype=grad_dtype, p=0.3, H=int(rng.choice([2, 3, 5])), seed=70 + seed,
              sigma=0.1, c_scale=0.25, wd_mult=[1, 0, 1, 0.5, 1] if seed % 2 else None, row_extra=seed % 2,
-             inner_nesterov=bool(seed % 3 == 0))
+             inner_nesterov=bool(seed % 3 == 0),
+             **(dict(outer_opt="adamw", outer_lr=0.02, outer_beta1=0.8, outer_beta2=0.95, outer_eps=0.05, outer_weight_decay=0.05)
+                if outer_adamw else {}))
     dev = torch.device("cuda:0")
     log = []
     shared = False        # a DDP warm-up keeps the InnerOPT state (and with ddp_shared the model) once, until a later call needs the rows
@@ -90,7 +93,9 @@ def test_random_call_sequence(seed):
             elif op == "finish":
                 r.lib.palsgd_ddp_finish()
             elif op == "outer_lr":
-                lr = float(rng.choice([0.0, 0.2, 0.7, 1.0]))
+                # AdamW outside turns a difference d between the two sides' Delta into outer_lr * d / (|Delta| + eps)
+                # on x: its rates stay below eps = 0.05 here, so that the factor is below 1
+                lr = float(rng.choice([0.0, 0.005, 0.01, 0.02] if outer_adamw else [0.0, 0.2, 0.7, 1.0]))
                 r.ora.set_outer_lr(lr)
                 r.lib.palsgd_set_outer_lr(lr)
             elif op == "capturable":                            # a few steps driven by the device-resident schedule

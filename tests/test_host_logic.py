@@ -55,6 +55,8 @@ def test_init_rejects_bad_arguments_without_touching_the_device():
         dict(cfg=dict(inner="sgdm", momentum=1.0)), dict(cfg=dict(outer_momentum=1.5)),
         dict(cfg=dict(outer_lr=float("inf"))), dict(cfg=dict(weight_decay=-1.0)),
         dict(cfg=dict(wd_mult=[1.0, float("nan")])),
+        dict(cfg=dict(outer_opt="adamw")),                       # no OV buffer
+        dict(cfg=dict(outer_opt="adamw", outer_beta2=1.0), buf=dict(OV=FAKE)), dict(cfg=dict(outer_opt=7)),
         dict(buf=dict(X=None)), dict(buf=dict(V=None)), dict(buf=dict(G=FAKE + 4)), dict(buf=dict(row_stride=192)),
         dict(buf=dict(row_stride=256 + 32)),
     ]
@@ -76,6 +78,9 @@ def test_init_rejects_bad_arguments_without_touching_the_device():
         cfg = make_config(2, numels)
         P = C.c_uint64()
         assert lib().palsgd_layout(C.byref(cfg), C.byref(P), None) == binding.PALSGD_EINVAL
+    st, out = _init(make_config(2, [10], outer_opt="adamw"), OV=FAKE)
+    assert st == binding.PALSGD_OK
+    lib().palsgd_destroy(out)
     # SGD-momentum needs no V
     st, out = _init(make_config(2, [10], inner="sgdm"), V=None)
     assert st == binding.PALSGD_OK
