@@ -80,6 +80,8 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     from paper_2504_18454_amd import binding
 
     binding.lib()                                       # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU is visible; the PALSGD update path runs in HIP kernels only (there is no CPU path)")
     dev = torch.device("cuda:0")
     cfg = make_config(w.K, w.numels, inner=w.inner, grad_dtype=w.grad_dtype, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
                       weight_decay=w.weight_decay, momentum=w.momentum, p=w.p, H=w.H,
