@@ -164,18 +164,34 @@ def palsgd_layout(cfg: Config):
     return int(P.value), [int(offs[j]) for j in range(cfg.n_tensors)]
 
 
-def _u8(mask):
+def _u8(mask, n):
+    """Host array of n bytes for the C side (which reads exactly n), or NULL."""
     if mask is None:
         return None, None
     a = np.ascontiguousarray(mask, dtype=np.uint8)
+    if a.shape != (n,):
+        raise ValueError(f"expected {n} entries (one per worker), got shape {a.shape}")
     return a, a.ctypes.data_as(C.POINTER(C.c_uint8))
 
 
-def _f32(v):
+def _f32(v, n):
+    """Host array of n floats for the C side (which reads exactly n), or NULL."""
     if v is None:
         return None, None
     a = np.ascontiguousarray(v, dtype=np.float32)
+    if a.shape != (n,):
+        raise ValueError(f"expected {n} entries (one per worker), got shape {a.shape}")
     return a, a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+def _dev_f32(t, n, what):
+    """Device address of a float32 array with room for n values: a torch CUDA tensor (checked) or a raw address."""
+    if t is None or isinstance(t, int):
+        return t
+    import torch
+    if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() >= n):
+        raise ValueError(f"{what}: expected a contiguous float32 CUDA tensor of at least {n} elements")
+    return t.data_ptr()
 
 
 def _stream_handle(stream) -> Optional[int]:
@@ -199,11 +215,31 @@ class Palsgd:
         self._tensors = (X, M, V, G, XG, OM, OV, x0)      # keep references
         self.cfg = cfg
         self.K = int(cfg.K)
+        self._check_tensors(cfg, X, M, V, G, XG, OM, OV, x0, int(row_stride))
         buf = Buffers(ptr(X), ptr(M), ptr(V), ptr(G), ptr(XG), ptr(OM), int(row_stride), ptr(OV))
         out = C.c_void_p()
         st = lib().palsgd_init(C.byref(cfg), C.byref(buf), ptr(x0), _stream_handle(stream), C.byref(out))
         _check(st, None)
         self._ctx = out
+
+    @staticmethod
+    def _check_tensors(cfg, X, M, V, G, XG, OM, OV, x0, row_stride):
+        """Sizes and dtypes of the buffers that are torch tensors (raw addresses cannot be checked): the kernels
+        index K rows of row_stride elements and trust the caller's allocation."""
+        import torch
+        P_padded, _ = palsgd_layout(cfg)
+        K = int(cfg.K)
+        rows = (K - 1) * row_stride + P_padded if row_stride >= P_padded else 0   # init rejects a short stride itself
+        gdt = torch.float32 if cfg.grad_dtype == GRAD["f32"] else torch.bfloat16
+        for name, t, need, dt in (("X", X, rows, torch.float32), ("M", M, rows, torch.float32), ("V", V, rows, torch.float32),
+                                  ("G", G, rows, gdt), ("XG", XG, P_padded, torch.float32),
+                                  ("OM", OM, P_padded, torch.float32), ("OV", OV, P_padded, torch.float32),
+                                  ("x0", x0, P_padded, torch.float32)):
+            if t is None or isinstance(t, int):
+                continue
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and t.numel() >= need):
+                raise ValueError(f"{name}: expected a contiguous {dt} CUDA tensor of at least {need} elements, got "
+                                 f"{t.dtype} {tuple(t.shape)} on {t.device}")
 
     # -- the C entry points, same names ------------------------------------------------
     def palsgd_draw(self, t: int) -> np.ndarray:
@@ -212,33 +248,33 @@ class Palsgd:
         return mask
 
     def palsgd_inner_step(self, t, alpha_t, grad_scale=None, mask_override=None, stream=None):
-        gs, gsp = _f32(grad_scale)
-        mo, mop = _u8(mask_override)
+        gs, gsp = _f32(grad_scale, self.K)
+        mo, mop = _u8(mask_override, self.K)
         _check(lib().palsgd_inner_step(self._ctx, int(t), alpha_t, gsp, mop, _stream_handle(stream)), self._ctx)
 
     def palsgd_pseudo_sync(self, t, alpha_t, eta_t, mask_override=None, stream=None):
-        mo, mop = _u8(mask_override)
+        mo, mop = _u8(mask_override, self.K)
         _check(lib().palsgd_pseudo_sync(self._ctx, int(t), alpha_t, eta_t, mop, _stream_handle(stream)), self._ctx)
 
     def palsgd_step(self, t, alpha_t, eta_t, grad_scale=None, mask_override=None, stream=None):
-        gs, gsp = _f32(grad_scale)
-        mo, mop = _u8(mask_override)
+        gs, gsp = _f32(grad_scale, self.K)
+        mo, mop = _u8(mask_override, self.K)
         _check(lib().palsgd_step(self._ctx, int(t), alpha_t, eta_t, gsp, mop, _stream_handle(stream)), self._ctx)
 
     def palsgd_step_sync(self, t, alpha_t, eta_t, grad_scale=None, mask_override=None, stream=None):
-        gs, gsp = _f32(grad_scale)
-        mo, mop = _u8(mask_override)
+        gs, gsp = _f32(grad_scale, self.K)
+        mo, mop = _u8(mask_override, self.K)
         _check(lib().palsgd_step_sync(self._ctx, int(t), alpha_t, eta_t, gsp, mop, _stream_handle(stream)), self._ctx)
 
     def palsgd_outer_step(self, t, stream=None):
         _check(lib().palsgd_outer_step(self._ctx, int(t), _stream_handle(stream)), self._ctx)
 
     def palsgd_ddp_step(self, t, alpha_t, grad_scale=None, stream=None):
-        gs, gsp = _f32(grad_scale)
+        gs, gsp = _f32(grad_scale, self.K)
         _check(lib().palsgd_ddp_step(self._ctx, int(t), alpha_t, gsp, _stream_handle(stream)), self._ctx)
 
     def palsgd_ddp_step_shared(self, t, alpha_t, grad_scale=None, stream=None):
-        gs, gsp = _f32(grad_scale)
+        gs, gsp = _f32(grad_scale, self.K)
         _check(lib().palsgd_ddp_step_shared(self._ctx, int(t), alpha_t, gsp, _stream_handle(stream)), self._ctx)
 
     def palsgd_ddp_finish(self, stream=None):
@@ -246,23 +282,23 @@ class Palsgd:
 
     def palsgd_clip_grad_norm(self, max_norm, norms_out=None, stream=None):
         """norms_out: torch CUDA float32 tensor of K elements (or a device address), or None."""
-        ptr = None if norms_out is None else (norms_out if isinstance(norms_out, int) else norms_out.data_ptr())
+        ptr = _dev_f32(norms_out, self.K, "norms_out")
         _check(lib().palsgd_clip_grad_norm(self._ctx, max_norm, ptr, _stream_handle(stream)), self._ctx)
 
     def palsgd_clip_mean_grad_norm(self, max_norm, grad_scale=None, norm_out=None, stream=None):
         """norm_out: torch CUDA float32 tensor of 1 element (or a device address), or None."""
-        gs, gsp = _f32(grad_scale)
-        ptr = None if norm_out is None else (norm_out if isinstance(norm_out, int) else norm_out.data_ptr())
+        gs, gsp = _f32(grad_scale, self.K)
+        ptr = _dev_f32(norm_out, 1, "norm_out")
         _check(lib().palsgd_clip_mean_grad_norm(self._ctx, max_norm, gsp, ptr, _stream_handle(stream)), self._ctx)
 
     def palsgd_diagnostics(self, out, stream=None):
         """out: torch CUDA float32 tensor of 2 elements (or a device address): Xi, |Delta|^2."""
-        ptr = out if isinstance(out, int) else out.data_ptr()
+        ptr = _dev_f32(out, 2, "out")
         _check(lib().palsgd_diagnostics(self._ctx, ptr, _stream_handle(stream)), self._ctx)
 
     def palsgd_outer_step_diag(self, t, out, stream=None):
         """Outer step + diagnostics taken just before it; out as in palsgd_diagnostics."""
-        ptr = out if isinstance(out, int) else out.data_ptr()
+        ptr = _dev_f32(out, 2, "out")
         _check(lib().palsgd_outer_step_diag(self._ctx, int(t), ptr, _stream_handle(stream)), self._ctx)
 
     def palsgd_capturable_begin(self, t0, stream=None):
@@ -270,7 +306,7 @@ class Palsgd:
 
     def palsgd_step_capturable(self, alpha_eta, stream=None):
         """alpha_eta: torch CUDA float32 tensor {alpha_t, eta_t} (or a device address)."""
-        ptr = alpha_eta if isinstance(alpha_eta, int) else alpha_eta.data_ptr()
+        ptr = _dev_f32(alpha_eta, 2, "alpha_eta")
         _check(lib().palsgd_step_capturable(self._ctx, ptr, _stream_handle(stream)), self._ctx)
 
     def palsgd_capturable_end(self, stream=None) -> int:
@@ -285,6 +321,8 @@ class Palsgd:
         return [int(v) for v in tau], int(n_outer.value)
 
     def palsgd_set_state(self, tau, n_outer):
+        if len(tau) != self.K:
+            raise ValueError(f"expected {self.K} step counts (one per worker), got {len(tau)}")
         arr = (C.c_uint64 * self.K)(*[int(v) for v in tau])
         _check(lib().palsgd_set_state(self._ctx, arr, int(n_outer)), self._ctx)
 

@@ -231,6 +231,40 @@ def test_config_gptneo1p3b_k8_sampled():
     _sampled("gptneo1p3b_k8", steps=128, per_edge=256, n_random=1 << 16)
 
 
+def test_binding_argument_checks():
+    """What the C side cannot check (it gets plain pointers) the binding checks before the call: tensor sizes and
+    dtypes, lengths of the per-worker host arrays."""
+    from paper_2504_18454_amd import Palsgd, make_config, palsgd_layout
+    K = 3
+    cfg = make_config(K, [1000, 64], grad_dtype="bf16")
+    row, _ = palsgd_layout(cfg)
+    dev = "cuda:0"
+    f = lambda *shape: torch.zeros(*shape, device=dev)
+    good = dict(X=f(K, row), M=f(K, row), V=f(K, row), G=torch.zeros(K, row, dtype=torch.bfloat16, device=dev),
+                XG=f(row), OM=f(row))
+    def make(**over):
+        b = dict(good); b.update(over)
+        return Palsgd(cfg, b["X"], b["M"], b["V"], b["G"], b["XG"], b["OM"], row, x0=f(row))
+    for bad in (dict(G=f(K, row)), dict(X=f(K - 1, row)), dict(XG=f(row - 64)), dict(M=f(K, row).double()),
+                dict(V=f(K, 2 * row)[:, :row])):
+        with pytest.raises(ValueError):
+            make(**bad)
+    ctx = make()
+    with pytest.raises(ValueError):
+        ctx.palsgd_step(0, 1e-3, 16.0, grad_scale=[1.0] * (K - 1))
+    with pytest.raises(ValueError):
+        ctx.palsgd_step(0, 1e-3, 16.0, mask_override=[0] * (K + 1))
+    with pytest.raises(ValueError):
+        ctx.palsgd_set_state([0] * (K - 1), 0)
+    with pytest.raises(ValueError):
+        ctx.palsgd_clip_grad_norm(1.0, torch.zeros(K - 1, device=dev))
+    with pytest.raises(ValueError):
+        ctx.palsgd_diagnostics(torch.zeros(2, device=dev, dtype=torch.float64))
+    ctx.palsgd_step(0, 1e-3, 16.0)
+    torch.cuda.synchronize()
+    ctx.palsgd_destroy()
+
+
 def _every_element(name, steps=None, fused_sync=False, B=1 << 16):
     """Full-size buffers, the benchmark's launch configuration, inputs periodic along the row: all elements of
     all state arrays are compared with the oracle (which runs one period), after all steps."""

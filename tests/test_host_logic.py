@@ -87,6 +87,15 @@ def test_init_rejects_bad_arguments_without_touching_the_device():
     lib().palsgd_destroy(out)
 
 
+def test_binding_refuses_tensors_the_kernels_could_not_index():
+    import torch
+    from paper_2504_18454_amd import Palsgd
+    cfg = make_config(2, [100])                             # P_padded = 256
+    host = torch.zeros(2, 256)
+    with pytest.raises(ValueError, match="CUDA tensor"):    # host memory where device memory is expected
+        Palsgd(cfg, host, host, host, host, host[0], host[0], 256)
+
+
 def test_draws_equal_oracle_bit_for_bit(oracle_mod):
     for K, p, seed in ((4, 0.1, 0), (8, 0.05, 1), (16, 0.02, 3), (64, 0.25, 2 ** 63 + 5), (1, 0.5, 9), (3, 0.0, 4)):
         st, ctx = _init(make_config(K, [128], p=p, seed=seed))
