@@ -69,7 +69,7 @@ typedef struct {
                                      multiplier on weight_decay                             */
     int32_t inner;                /* palsgd_inner_opt                                       */
     int32_t grad_dtype;           /* palsgd_grad_dtype                                      */
-    float beta1, beta2, eps;      /* AdamW moments and epsilon                              */
+    float beta1, beta2, eps;      /* AdamW moments and epsilon (eps > 0: zero padding stays zero) */
     float weight_decay;           /* AdamW: decoupled; SGDM: added to the gradient          */
     float momentum;               /* SGDM momentum (dampening 0)                            */
     int32_t inner_nesterov;       /* SGDM: 1 = Nesterov form x -= lr (d + mu buf), 0 = heavy

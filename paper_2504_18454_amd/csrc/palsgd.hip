@@ -452,7 +452,8 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
     if (cfg->inner == PALSGD_INNER_ADAMW) {
         PALSGD_REQUIRE(cfg->beta1 >= 0.0f && cfg->beta1 < 1.0f, "beta1 must satisfy 0 <= beta1 < 1");
         PALSGD_REQUIRE(cfg->beta2 >= 0.0f && cfg->beta2 < 1.0f, "beta2 must satisfy 0 <= beta2 < 1");
-        PALSGD_REQUIRE(std::isfinite(cfg->eps) && cfg->eps >= 0.0f, "eps must be finite, >= 0");
+        // > 0: the padding between tensors holds g = m = v = 0 and must stay 0, not become 0/0
+        PALSGD_REQUIRE(std::isfinite(cfg->eps) && cfg->eps > 0.0f, "eps must be finite, > 0");
         PALSGD_REQUIRE(buf->V != nullptr, "V buffer is required by AdamW");
     } else {
         PALSGD_REQUIRE(std::isfinite(cfg->momentum) && cfg->momentum >= 0.0f && cfg->momentum < 1.0f,
@@ -465,7 +466,7 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
     if (cfg->outer_opt == PALSGD_OUTER_ADAMW) {
         PALSGD_REQUIRE(cfg->outer_beta1 >= 0.0f && cfg->outer_beta1 < 1.0f, "outer_beta1 must satisfy 0 <= outer_beta1 < 1");
         PALSGD_REQUIRE(cfg->outer_beta2 >= 0.0f && cfg->outer_beta2 < 1.0f, "outer_beta2 must satisfy 0 <= outer_beta2 < 1");
-        PALSGD_REQUIRE(std::isfinite(cfg->outer_eps) && cfg->outer_eps >= 0.0f, "outer_eps must be finite, >= 0");
+        PALSGD_REQUIRE(std::isfinite(cfg->outer_eps) && cfg->outer_eps > 0.0f, "outer_eps must be finite, > 0");
         PALSGD_REQUIRE(std::isfinite(cfg->outer_weight_decay) && cfg->outer_weight_decay >= 0.0f,
                        "outer_weight_decay must be finite, >= 0");
         PALSGD_REQUIRE(buf->OV != nullptr && aligned16(buf->OV), "OV buffer (16-byte aligned) is required by OuterOPT = AdamW");

@@ -51,7 +51,8 @@ def _init(cfg, **over):
 def test_init_rejects_bad_arguments_without_touching_the_device():
     bad = [
         dict(cfg=dict(K=0)), dict(cfg=dict(K=65)), dict(cfg=dict(H=0)), dict(cfg=dict(p=1.0)), dict(cfg=dict(p=-0.1)),
-        dict(cfg=dict(beta1=1.0)), dict(cfg=dict(beta2=-0.1)), dict(cfg=dict(eps=float("nan"))),
+        dict(cfg=dict(beta1=1.0)), dict(cfg=dict(beta2=-0.1)), dict(cfg=dict(eps=float("nan"))), dict(cfg=dict(eps=0.0)),
+        dict(cfg=dict(outer_opt="adamw", outer_eps=0.0), buf=dict(OV=FAKE)),
         dict(cfg=dict(inner="sgdm", momentum=1.0)), dict(cfg=dict(outer_momentum=1.5)),
         dict(cfg=dict(outer_lr=float("inf"))), dict(cfg=dict(weight_decay=-1.0)),
         dict(cfg=dict(wd_mult=[1.0, float("nan")])),
