@@ -312,8 +312,14 @@ def main():
     r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph, wd_mult, a.fused_sync, a.outer_adamw)
     cpu = None
     if not a.no_cpu_baseline:
-        cpu = run_cpu_baseline(w)
-        one = run_cpu_baseline(w, slice_div=64, threads=1)       # the same loop on one core, smaller slice
+        # bounded sample: about K * 62M * (H+1) element updates for the all-threads leg whatever the workload
+        # (the benchmark configuration: half of every row), 1/32 of that for the one-core leg
+        budget = 8 * 62206080 * 65
+        div = 2
+        while w.K * (w.P // div) * (w.H + 1) > budget:
+            div *= 2
+        cpu = run_cpu_baseline(w, slice_div=div)
+        one = run_cpu_baseline(w, slice_div=32 * div, threads=1)  # the same loop on one core, smaller slice
         cpu["one_core"] = {"value": one["value"], "sample": one["sample"]}
         cpu["gpu_over_cpu"] = r["updates"] / r["elapsed"] / cpu["value"]       # context only: the roofline fraction is the measure
     gb = grad_bytes_per_elem(w.inner, w.grad_dtype)
