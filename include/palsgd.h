@@ -14,6 +14,7 @@
  *                      each step                             (Sec. 3, WorkerOPT eq.)
  *   XG[row_stride]     global model copy x                   (Sec. 4.1)
  *   OM[row_stride]     OuterOPT momentum buffer              (Sec. 4.3)
+ *   OV[row_stride]     OuterOPT second moment (only with OuterOPT = AdamW, else NULL)
  * A row is the flat concatenation of the model's tensors; every tensor starts at a
  * multiple of 64 elements and the padded row length P_padded is a multiple of 256
  * (palsgd_layout).  Padding elements must be zero in x0 and in G; the update keeps them
@@ -25,14 +26,18 @@
  *
  * Ownership: the library borrows the buffer pointers from palsgd_init until
  * palsgd_destroy and owns only its context, a device-side table of weight-decay
- * values (4 bytes per 64 elements of a row, made by the first gradient step and only
- * when tensor_wd_mult is not uniform), the scratch of the scalar reductions and the
+ * values (4 bytes per 64 elements of a row, made by palsgd_init and only when
+ * tensor_wd_mult is not uniform), the scratch of the scalar reductions and the
  * device schedule of the capturable mode.
  * Streams: `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
  * device work is enqueued on it; calls return without waiting.
  * Errors: every entry point returns a palsgd_status and never aborts; argument
  * errors are found before any launch and leave all state untouched.  The text of
- * the last error of a context is available through palsgd_last_error.
+ * the last error of a context is available through palsgd_last_error.  The library
+ * gets plain pointers: it checks alignment and NULLs, not sizes; every row buffer must
+ * hold (K-1) * row_stride + P_padded elements, every single-row buffer P_padded.
+ * palsgd_destroy frees the library's device memory: the caller waits for the streams
+ * it used first.
  * Threads: a context must not be used from two threads at once.
  */
 #ifndef PALSGD_H
