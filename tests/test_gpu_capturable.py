@@ -58,13 +58,18 @@ def test_host_driven_calls_are_refused_while_device_resident():
     r.close()
 
 
-@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
-def test_replayed_graph_of_a_window_follows_alg1(grad_dtype):
-    """One captured window [H x (load gradients, local update), outer step] replayed for consecutive windows:
-    t, the draws and the step counts advance on the device, alpha changes between replays through the device
-    array, and every replay is compared with the oracle."""
+@pytest.mark.parametrize("grad_dtype,clip", [("f32", None), ("bf16", None), ("f32", 20.0), ("bf16", 20.0)])
+def test_replayed_graph_of_a_window_follows_alg1(grad_dtype, clip):
+    """One captured window [H x (load gradients, (clip), local update), outer step] replayed for consecutive
+    windows: t, the draws and the step counts advance on the device, alpha changes between replays through the
+    device array, the clipping scales are recomputed on the device by every replay, and every replay is compared
+    with the oracle."""
+    import oracle
     H, K = 3, 4
-    r = _run(K=K, numels=RAGGED, grad_dtype=grad_dtype, p=0.3, H=H, seed=61, sigma=0.05, wd_mult=[1, 0, 1, 1, 0.5, 1, 0])
+    r = _run(K=K, numels=RAGGED, grad_dtype=grad_dtype, p=0.3, H=H, seed=61, wd_mult=[1, 0, 1, 1, 0.5, 1, 0],
+             **(dict(sigma=0.1, c_scale=0.25) if clip else dict(sigma=0.05)))
+    if clip:
+        r.lib.palsgd_clip_grad_norm(clip)                # allocates the reduction scratch: not inside a capture
     stage = torch.zeros((H,) + tuple(r.G.shape), dtype=r.G.dtype, device="cuda:0")
     ae = torch.tensor([r.alpha, r.eta], dtype=torch.float32, device="cuda:0")
     r.lib.palsgd_capturable_begin(0)
@@ -75,15 +80,22 @@ def test_replayed_graph_of_a_window_follows_alg1(grad_dtype):
     with torch.cuda.graph(g, stream=s):
         for i in range(H):
             r.G.copy_(stage[i])
+            if clip:
+                r.lib.palsgd_clip_grad_norm(clip)
             r.lib.palsgd_step_capturable(ae)
         r.lib.palsgd_outer_step(0)
     torch.cuda.synchronize()
+    clipped = False
     for w in range(5):
         alpha = float(np.float32(r.alpha * (1.0 + 0.25 * w)))          # a learning-rate schedule across windows
         for i in range(H):
             gd = r.oracle_side_gradients()
             stage[i, :, :r.row].copy_(gd)
-            _, synced = r.ora.iteration(r.t, alpha, r.eta)
+            scales = None
+            if clip:
+                scales = np.array([oracle.clip_scale(v, float(np.float32(clip))) for v in r.ora.grad_norms()])
+                clipped = clipped or bool((scales < 1).any())
+            _, synced = r.ora.iteration(r.t, alpha, r.eta, grad_scale=scales)
             r.t += 1
         assert synced
         ae.copy_(torch.tensor([alpha, r.eta], dtype=torch.float32))
@@ -95,6 +107,7 @@ def test_replayed_graph_of_a_window_follows_alg1(grad_dtype):
     assert r.lib.palsgd_capturable_end() == r.t
     tau, _ = r.lib.palsgd_get_state()
     assert tau == [int(v) for v in r.ora.tau]
+    assert clipped == bool(clip)                                       # the threshold did bite
     r.close()
 
 
