@@ -24,6 +24,12 @@
  *     the workers share one starting point every H local steps; App. A.5, proof
  *     of Lemma 4: x^(t) = x_k^(t-)).
  *
+ * Around Alg. 1, each with its own routine and pins: the DDP step of the
+ * warm-up phase (Sec. 3.1, Sec. 4.3), gradient clipping by the global norm of
+ * one worker's gradient and of the averaged gradient (App. B), the consensus
+ * distance and |Delta|^2 of the analysis (App. A.3), the Nesterov form of the
+ * SGD-momentum InnerOPT and AdamW as OuterOPT (the optimizer pairs of App. C).
+ *
  * Precision: state (x_k, x, optimizer moments) is stored in fp32, the storage
  * type of the device path.  Every element update reads the stored values,
  * evaluates the whole update in fp64 and rounds to fp32 once per stored value.
