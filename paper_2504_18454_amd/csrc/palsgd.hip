@@ -396,11 +396,11 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
 template <int INNER, int GDT>
 void launch_sync_step(palsgd_ctx* c, const StepArgs& args, const float* clip, const OuterArgs& a, hipStream_t st) {
     const uint32_t K = c->cfg.K;
-    // Per batch of four replicas: their state in, their InnerOPT state out (the K+2 rows of x leave at the
-    // end). A wavefront has about half of a batch in flight at a time: measured best 6-7 for AdamW with
-    // bf16 gradients, 8-12 for SGD-momentum, which this rule gives (7 and 10).
-    const uint32_t per_batch = kSyncBatch * ((INNER == PALSGD_INNER_ADAMW ? 20u : 12u) + (GDT == PALSGD_GRAD_F32 ? 4u : 2u));
-    const uint32_t waves = c->outer_waves ? c->outer_waves : auto_waves(per_batch * kTile / 2, 6);
+    // Resident wavefronts per CU, from sweeps of this kernel: 4-6 for AdamW at K <= 8 (two batches of four
+    // replicas per wavefront), 8-10 from K = 16 up, 8-12 for SGD-momentum.
+    (void)GDT;
+    const uint32_t best = INNER == PALSGD_INNER_ADAMW ? (K <= 8 ? 6u : 8u) : 10u;
+    const uint32_t waves = c->outer_waves ? c->outer_waves : best;
     Hyper h = hyper_of(c);
     const palsgd_buffers& b = c->buf;
     const uint32_t lds = lds_cap(waves, 0);
