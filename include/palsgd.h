@@ -201,7 +201,9 @@ palsgd_status palsgd_ddp_step_shared(palsgd_ctx *ctx, uint64_t t, float alpha_t,
 
 /* End of the warm-up made explicit: copies worker 0's InnerOPT state into rows 1..K-1 of
  * M, V, and XG into the K rows of X, where DDP steps left them stale (one launch); no
- * launch otherwise. */
+ * launch otherwise.  Call it before capturing PALSGD steps into a HIP graph: left to the
+ * first captured call, the broadcast would be part of the graph and every replay would
+ * hand the workers the common state again. */
 palsgd_status palsgd_ddp_finish(palsgd_ctx *ctx, void *stream);
 
 /* Gradient clipping by the global L2 norm of each worker's gradient (App. B says the GPT-Neo runs
