@@ -26,9 +26,11 @@
  *
  * Ownership: the library borrows the buffer pointers from palsgd_init until
  * palsgd_destroy and owns only its context, a device-side table of weight-decay
- * values (4 bytes per 64 elements of a row, made by palsgd_init and only when
- * tensor_wd_mult is not uniform), the scratch of the scalar reductions and the
- * device schedule of the capturable mode.
+ * values (4 bytes per 64 elements of a row, only when tensor_wd_mult is not
+ * uniform), the scratch of the scalar reductions (P_padded/32 bytes, or
+ * K * P_padded/1024 if that is more) and the 2.3 KB device schedule of the capturable
+ * mode.  palsgd_init allocates all of it; no other entry point allocates or frees
+ * device memory, so every one of them may be the first call inside a stream capture.
  * Streams: `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
  * device work is enqueued on it; calls return without waiting.
  * Errors: every entry point returns a palsgd_status and never aborts; argument
@@ -110,11 +112,13 @@ palsgd_status palsgd_layout(const palsgd_config *cfg, uint64_t *P_padded, uint64
  * (device, P_padded floats, padding zero) is not NULL, it is copied into XG and every
  * row of X, and M, V, OM are cleared, on `stream`; if NULL the buffers are taken as
  * they are (resume).  EINVAL: K outside 1..64, H == 0, p outside [0,1), NULL or
- * misaligned buffers, row_stride < P_padded or not a multiple of 64, P_padded > 2^38,
+ * misaligned buffers, row_stride < P_padded or not a multiple of 64, P_padded > 2^33,
  * beta/eps/momentum outside their ranges, V == NULL with AdamW.  When the weight-decay
  * multipliers differ between tensors (and weight_decay != 0) a device table of one float
- * per 64 row elements is allocated and filled here (ENOMEM / EHIP if that fails), so
- * that no later call allocates on the step path.  On failure *out is NULL. */
+ * per 64 row elements is allocated and filled here, and so are the reduction scratch and
+ * the device schedule (ENOMEM / EHIP if that fails): no later call allocates.  On failure
+ * *out is NULL.  With no GPU visible the context is still created, for palsgd_draw and the
+ * scalar state calls (host-side checks); every call of it that would launch returns EHIP. */
 palsgd_status palsgd_init(const palsgd_config *cfg, const palsgd_buffers *buf, const float *x0_dev,
                           void *stream, palsgd_ctx **out);
 
@@ -160,8 +164,9 @@ palsgd_status palsgd_step_sync(palsgd_ctx *ctx, uint64_t t, float alpha_t, float
  * OM <- b1 OM + (1-b1) Delta, OV <- b2 OV + (1-b2) Delta^2,
  * XG <- XG - outer_lr ((OM/(1-b1^n)) / (sqrt(OV/(1-b2^n)) + eps) + wd XG), n = number of
  * this outer step (from 1; part of palsgd_get_state / palsgd_set_state).  The bias
- * corrections are launch arguments computed from n on the host, so an outer step with
- * AdamW that was captured into a HIP graph must not be replayed.  The caller decides when
+ * corrections are launch arguments computed from n on the host, so with AdamW this call
+ * (and palsgd_step_sync, palsgd_outer_step_diag) returns ESTATE while `stream` is being
+ * captured into a HIP graph.  The caller decides when
  * ((t+1) mod H == 0 in Alg. 1); t is recorded for diagnostics only. */
 palsgd_status palsgd_outer_step(palsgd_ctx *ctx, uint64_t t, void *stream);
 
@@ -214,9 +219,9 @@ palsgd_status palsgd_ddp_finish(palsgd_ctx *ctx, void *stream);
  * of grad_scale[k]) and forgets the scales, whether or not worker k (or any worker) takes
  * the gradient branch in that step: they belong to that step's gradients.
  * norms_out_dev: device array of K floats that receives the norms, or NULL.
- * The first call allocates the library's reduction scratch (about P_padded/128 floats);
- * palsgd_clip_grad_norm, palsgd_diagnostics and palsgd_outer_step_diag share it and must
- * be issued on one stream.
+ * palsgd_clip_grad_norm, palsgd_clip_mean_grad_norm, palsgd_diagnostics and
+ * palsgd_outer_step_diag share the context's reduction scratch and must be issued on one
+ * stream.
  * EINVAL unless max_norm is finite and > 0. */
 palsgd_status palsgd_clip_grad_norm(palsgd_ctx *ctx, float max_norm, float *norms_out_dev, void *stream);
 
@@ -241,15 +246,17 @@ palsgd_status palsgd_diagnostics(palsgd_ctx *ctx, float *out_dev, void *stream);
  * draws b_k^(t) (same hash as palsgd_draw), each worker's InnerOPT step count and AdamW
  * bias corrections live in library-owned device memory and are advanced on the device.
  *
- * palsgd_capturable_begin: uploads t0 (index of the next step) and the current step counts;
- *   allocates the device schedule on its first call, so call it before the capture starts.
+ * palsgd_capturable_begin: uploads t0 (index of the next step) and the current step counts
+ *   (one small launch on `stream`).  ESTATE if the schedule is already device-resident.
  * palsgd_step_capturable: step t of Alg. 1 for all K workers, as palsgd_step with
  *   grad_scale == NULL and no mask override, then t <- t+1, in two launches.  alpha_eta_dev:
  *   device array {alpha_t, eta_t}, read when the step runs (the caller may update it between
  *   replays: learning-rate schedules).  Clipping scales armed at the time of the call are
  *   applied.  Safe to capture; palsgd_outer_step, palsgd_outer_step_diag,
- *   palsgd_clip_grad_norm and palsgd_diagnostics are capturable as they are (their first
- *   calls allocate, so make one call of each kind used before the capture).
+ *   palsgd_clip_grad_norm and palsgd_diagnostics are capturable as they are, with no call
+ *   needed before the capture.  The host-side count of outer steps (palsgd_get_state) advances
+ *   when palsgd_outer_step is called, not when a graph that holds it is replayed: a caller that
+ *   replays outer steps keeps that count itself.
  * palsgd_capturable_end: waits for `stream`, reads t and the step counts back (t_out may be
  *   NULL) and returns the context to host-driven calls.
  * While the schedule is device-resident, palsgd_inner_step, palsgd_pseudo_sync, palsgd_step,
@@ -260,7 +267,12 @@ palsgd_status palsgd_step_capturable(palsgd_ctx *ctx, const float *alpha_eta_dev
 palsgd_status palsgd_capturable_end(palsgd_ctx *ctx, uint64_t *t_out, void *stream);
 
 /* Host-side scalar state for checkpoint / resume: tau[k] = gradient steps worker k
- * has taken (drives AdamW's bias correction), n_outer = outer steps taken. */
+ * has taken (drives AdamW's bias correction), n_outer = outer steps taken.  Together with
+ * the caller's buffers this is the whole state of a run.  After DDP warm-up steps the
+ * buffers are not yet complete (rows 1..K-1 of M, V, and after palsgd_ddp_step_shared the
+ * rows of X, are filled by the broadcast that ends the warm-up): palsgd_get_state returns
+ * ESTATE until palsgd_ddp_finish or the first PALSGD call has run that broadcast, so call
+ * palsgd_ddp_finish before saving a checkpoint in the warm-up phase. */
 palsgd_status palsgd_get_state(const palsgd_ctx *ctx, uint64_t *tau, uint64_t *n_outer);
 palsgd_status palsgd_set_state(palsgd_ctx *ctx, const uint64_t *tau, uint64_t n_outer);
 

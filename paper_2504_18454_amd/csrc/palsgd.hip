@@ -94,18 +94,20 @@ struct palsgd_ctx {
     bool model_shared = false;     // after palsgd_ddp_step_shared: the rows of X are stale, the model is XG
     void* d_schedule = nullptr;    // DevSchedule of the graph-capturable mode
     bool capturable = false;       // between palsgd_capturable_begin and palsgd_capturable_end
+    bool host_only = false;        // created with no GPU visible: draws and scalar state only, every launch is refused
     uint32_t step_waves = 0;       // cap on resident wavefronts per CU, 0 = derive from bytes per wavefront
     uint32_t outer_waves = 0;
     uint32_t outer_variant = 0;
     uint64_t tau[PALSGD_MAX_K] = {0};
     uint64_t n_outer = 0;
     uint64_t last_outer_t = 0;
-    char error[256] = "";
+    mutable char error[256] = "";  // written by const entry points too
 };
 
 namespace {
 
-constexpr uint64_t kMaxRow = 1ull << 38;  // keeps every grid dimension below 2^31
+// One lane per four elements and fewer than 2^32 work-items per launch dimension: rows below 2^34 elements.
+constexpr uint64_t kMaxRow = 1ull << 33;
 
 palsgd_status layout_impl(uint32_t n_tensors, const uint64_t* numel, uint64_t* P_padded, uint64_t* offs,
                           char* err) {
@@ -206,8 +208,43 @@ OuterArgs outer_args_of(const palsgd_ctx* c) {
     return a;
 }
 
+// True while `st` records a stream capture (a query that fails, as on the null stream next to another
+// stream's capture, counts as not capturing).
+bool stream_is_capturing(hipStream_t st) {
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &status) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return status != hipStreamCaptureStatusNone;
+}
+
+// OuterOPT = AdamW takes its bias corrections from the host-side outer-step count as launch arguments: a
+// captured launch would replay the first one's corrections for ever.
+palsgd_status refuse_captured_outer_adamw(palsgd_ctx* c, const char* who, hipStream_t st) {
+    if (c->cfg.outer_opt == PALSGD_OUTER_ADAMW && stream_is_capturing(st)) {
+        set_error(c->error, "%s: an outer step with OuterOPT = AdamW cannot be captured into a HIP graph "
+                            "(its bias corrections are launch arguments)", who);
+        return PALSGD_ESTATE;
+    }
+    return PALSGD_OK;
+}
+
 Hyper hyper_of(const palsgd_ctx* c) {
     return Hyper{c->cfg.beta1, c->cfg.beta2, c->cfg.eps, c->cfg.momentum, c->wd_eff0, c->cfg.inner_nesterov != 0};
+}
+
+// Every entry point calls this before its first launch: it refuses a context that was created without a
+// GPU, and it drops an error that another library may have left in the runtime, so that what check_launch
+// reads afterwards is the status of this entry point's own launches.
+palsgd_status begin_launches(palsgd_ctx* c, const char* who) {
+    if (c->host_only) {
+        set_error(c->error, "%s: no GPU was visible when this context was created; it serves palsgd_draw and "
+                            "the scalar state calls only", who);
+        return PALSGD_EHIP;
+    }
+    (void)hipGetLastError();
+    return PALSGD_OK;
 }
 
 palsgd_status check_launch(palsgd_ctx* c, const char* what) {
@@ -234,10 +271,12 @@ float* mean_clip_scale(palsgd_ctx* c) { return c->d_scratch + PALSGD_MAX_K; }
 double* scratch_fold(palsgd_ctx* c) { return (double*)(c->d_scratch + 2 * PALSGD_MAX_K); }
 float* scratch_partials(palsgd_ctx* c) { return c->d_scratch + 2 * PALSGD_MAX_K + 2 * PALSGD_MAX_K * kFold; }
 
-palsgd_status ensure_scratch(palsgd_ctx* c) {
-    if (c->d_scratch) return PALSGD_OK;
+// The library's device memory beyond the weight-decay table, all of it allocated by palsgd_init so that no
+// later call allocates: the reduction scratch (sized for the largest producer: K rows of norm partials, or two
+// partials per tile for the diagnostics fused into the outer step) and the device-resident schedule.
+palsgd_status alloc_device_state(palsgd_ctx* c) {
     uint64_t parts = (uint64_t)c->cfg.K * norm_parts(c);
-    if (parts < 2ull * tile_count(c)) parts = 2ull * tile_count(c);  // fused diagnostics: two per tile
+    if (parts < 2ull * tile_count(c)) parts = 2ull * tile_count(c);
     uint64_t floats = 2ull * PALSGD_MAX_K + 2ull * PALSGD_MAX_K * kFold + parts;
     float* d = nullptr;
     hipError_t e = hipMalloc(&d, floats * sizeof(float));
@@ -246,6 +285,12 @@ palsgd_status ensure_scratch(palsgd_ctx* c) {
         return PALSGD_ENOMEM;
     }
     c->d_scratch = d;
+    e = hipMalloc(&c->d_schedule, sizeof(DevSchedule));
+    if (e != hipSuccess) {
+        c->d_schedule = nullptr;
+        set_error(c->error, "hipMalloc(device schedule): %s", hipGetErrorString(e));
+        return PALSGD_ENOMEM;
+    }
     return PALSGD_OK;
 }
 
@@ -380,6 +425,8 @@ palsgd_status local_update(palsgd_ctx* c, const char* who, uint64_t t, float alp
     bool any_grad = false;
     for (uint32_t k = 0; k < K; ++k) any_grad = any_grad || stepped[k];
     hipStream_t st = (hipStream_t)stream;
+    rc = begin_launches(c, who);
+    if (rc != PALSGD_OK) return rc;
     rc = end_warmup_sharing(c, who, st);  // every worker needs its own model row and InnerOPT state from here on
     if (rc != PALSGD_OK) return rc;
     // clipping scales computed by palsgd_clip_grad_norm are consumed by the first gradient step after it
@@ -477,7 +524,7 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
                    "device buffers must be 16-byte aligned");
     PALSGD_REQUIRE(buf->row_stride >= P_padded && buf->row_stride % 64 == 0,
                    "row_stride must be a multiple of 64 and >= the padded row length");
-    PALSGD_REQUIRE(P_padded <= kMaxRow, "a row may hold at most 2^38 elements (one 256-element tile per workgroup)");
+    PALSGD_REQUIRE(P_padded <= kMaxRow, "a row may hold at most 2^33 elements (one lane per four elements in one launch dimension)");
     if (cfg->tensor_wd_mult)
         for (uint32_t j = 0; j < cfg->n_tensors; ++j)
             PALSGD_REQUIRE(std::isfinite(cfg->tensor_wd_mult[j]) && cfg->tensor_wd_mult[j] >= 0.0f,
@@ -502,21 +549,33 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
     if (cfg->weight_decay == 0.0f) c->wd_uniform = true;  // the multipliers multiply zero
     c->wd_eff0 = (float)((double)cfg->weight_decay * (double)c->wd_mult[0]);
     c->draw_threshold = (uint32_t)std::floor(cfg->p * 16777216.0);
-    if (!c->wd_uniform) {  // here, not at first use: a step may be the first call inside a stream capture
-        rc = build_wd_table(c);
+    // all device memory of the library is allocated here, never at first use: any later call may be the
+    // first one inside a stream capture, or come from a caller that must not allocate
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev <= 0) {
+        // no GPU: the context still answers palsgd_draw and the scalar state calls (what the host-side
+        // checks of this library use); every call that would launch returns PALSGD_EHIP
+        (void)hipGetLastError();
+        c->host_only = true;
+    } else {
+        rc = c->wd_uniform ? PALSGD_OK : build_wd_table(c);
+        if (rc == PALSGD_OK) rc = alloc_device_state(c);
         if (rc != PALSGD_OK) {
             memcpy(g_error, c->error, sizeof g_error);
             palsgd_destroy(c);
             return rc;
         }
+        (void)lds_per_cu();  // the device attribute query happens here as well
     }
     if (x0_dev) {
         uint64_t n4 = P_padded / 4;
         uint32_t blocks = (uint32_t)((n4 + kThreads - 1) / kThreads);
-        init_kernel<<<blocks, kThreads, 0, (hipStream_t)stream>>>(x0_dev, buf->X, buf->M, buf->V, buf->XG, buf->OM,
+        rc = begin_launches(c, "palsgd_init");
+        if (rc == PALSGD_OK)
+            init_kernel<<<blocks, kThreads, 0, (hipStream_t)stream>>>(x0_dev, buf->X, buf->M, buf->V, buf->XG, buf->OM,
                                                                   cfg->outer_opt == PALSGD_OUTER_ADAMW ? buf->OV : nullptr, n4,
                                                                   buf->row_stride, cfg->K);
-        rc = check_launch(c, "palsgd_init");
+        if (rc == PALSGD_OK) rc = check_launch(c, "palsgd_init");
         if (rc != PALSGD_OK) {
             memcpy(g_error, c->error, sizeof g_error);
             palsgd_destroy(c);
@@ -564,6 +623,9 @@ palsgd_status palsgd_step_sync(palsgd_ctx* ctx, uint64_t t, float alpha_t, float
     bool any_grad = false;
     for (uint32_t k = 0; k < K; ++k) any_grad = any_grad || stepped[k];
     hipStream_t st = (hipStream_t)stream;
+    rc = begin_launches(ctx, "palsgd_step_sync");
+    if (rc == PALSGD_OK) rc = refuse_captured_outer_adamw(ctx, "palsgd_step_sync", st);
+    if (rc != PALSGD_OK) return rc;
     rc = end_warmup_sharing(ctx, "palsgd_step_sync", st);
     if (rc != PALSGD_OK) return rc;
     const float* clip = any_grad && ctx->clip_armed ? clip_scales(ctx) : nullptr;
@@ -598,12 +660,12 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
     const palsgd_buffers& b = ctx->buf;
     const bool oadam = ctx->cfg.outer_opt == PALSGD_OUTER_ADAMW;
     {
-        palsgd_status rc = end_warmup_sharing(ctx, who, st);  // the rows of X are read here
+        palsgd_status rc = begin_launches(ctx, who);
+        if (rc == PALSGD_OK) rc = refuse_captured_outer_adamw(ctx, who, st);
+        if (rc == PALSGD_OK) rc = end_warmup_sharing(ctx, who, st);  // the rows of X are read here
         if (rc != PALSGD_OK) return rc;
     }
     if (diag_out_dev) {
-        palsgd_status rc = ensure_scratch(ctx);
-        if (rc != PALSGD_OK) return rc;
         const uint32_t tiles = tile_count(ctx);
         if (oadam)
             outer_kernel_walk<true, true><<<tiles, kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K,
@@ -698,6 +760,10 @@ static palsgd_status ddp_impl(palsgd_ctx* ctx, const char* who, float alpha_t, c
     hipStream_t st = (hipStream_t)stream;
     const palsgd_buffers& b = ctx->buf;
     const float* clip = ctx->clip_mean_armed ? mean_clip_scale(ctx) : nullptr;
+    {
+        palsgd_status rc = begin_launches(ctx, who);
+        if (rc != PALSGD_OK) return rc;
+    }
 #define PALSGD_DDP(I, D)                                                                                           \
     if (ctx->wd_uniform)                                                                                           \
         ddp_kernel<I, D, false><<<tiles, kWave, lds, st>>>(a, nullptr, b.X, b.M, b.V, b.G, b.XG, clip, n, b.row_stride, K, x_rows, h); \
@@ -732,35 +798,48 @@ palsgd_status palsgd_ddp_finish(palsgd_ctx* ctx, void* stream) {
         set_error(g_error, "palsgd_ddp_finish: NULL context");
         return PALSGD_EINVAL;
     }
-    return end_warmup_sharing(ctx, "palsgd_ddp_finish", (hipStream_t)stream);
+    palsgd_status rc = begin_launches(ctx, "palsgd_ddp_finish");
+    return rc != PALSGD_OK ? rc : end_warmup_sharing(ctx, "palsgd_ddp_finish", (hipStream_t)stream);
 }
 
-palsgd_status palsgd_clip_grad_norm(palsgd_ctx* ctx, float max_norm, float* norms_out_dev, void* stream) {
-    if (!ctx) {
-        set_error(g_error, "palsgd_clip_grad_norm: NULL context");
-        return PALSGD_EINVAL;
-    }
-    if (!(max_norm > 0.0f) || !std::isfinite(max_norm)) {
-        set_error(ctx->error, "palsgd_clip_grad_norm: max_norm must be finite and > 0");
-        return PALSGD_EINVAL;
-    }
-    palsgd_status rc = ensure_scratch(ctx);
-    if (rc != PALSGD_OK) return rc;
+// Body of palsgd_clip_grad_norm: `partial` holds K * norm_parts floats
+// and `fold` K * kFold doubles; the scales go to the context's own memory in both cases.
+static palsgd_status clip_norm_launches(palsgd_ctx* ctx, const char* who, float max_norm, float* norms_out_dev,
+                                        float* partial, double* fold, hipStream_t st) {
     const uint32_t K = ctx->cfg.K, per_row = norm_parts(ctx);
-    hipStream_t st = (hipStream_t)stream;
     dim3 grid(per_row, K);
     if (ctx->cfg.grad_dtype == PALSGD_GRAD_BF16)
-        sumsq_kernel<PALSGD_GRAD_BF16><<<grid, kWave, lds_cap(16, 0), st>>>(ctx->buf.G, scratch_partials(ctx), ctx->P_padded,
-                                                               ctx->buf.row_stride, per_row);
+        sumsq_kernel<PALSGD_GRAD_BF16><<<grid, kWave, lds_cap(16, 0), st>>>(ctx->buf.G, partial, ctx->P_padded,
+                                                                           ctx->buf.row_stride, per_row);
     else
-        sumsq_kernel<PALSGD_GRAD_F32><<<grid, kWave, lds_cap(16, 0), st>>>(ctx->buf.G, scratch_partials(ctx), ctx->P_padded,
-                                                              ctx->buf.row_stride, per_row);
-    fold_kernel<<<dim3(kFold, K), kThreads, 0, st>>>(scratch_partials(ctx), per_row, scratch_fold(ctx));
-    clip_finish_kernel<<<K, kThreads, 0, st>>>(scratch_fold(ctx), max_norm, clip_scales(ctx), norms_out_dev);
-    rc = check_launch(ctx, "palsgd_clip_grad_norm");
+        sumsq_kernel<PALSGD_GRAD_F32><<<grid, kWave, lds_cap(16, 0), st>>>(ctx->buf.G, partial, ctx->P_padded,
+                                                                          ctx->buf.row_stride, per_row);
+    fold_kernel<<<dim3(kFold, K), kThreads, 0, st>>>(partial, per_row, fold);
+    clip_finish_kernel<<<K, kThreads, 0, st>>>(fold, max_norm, clip_scales(ctx), norms_out_dev);
+    palsgd_status rc = check_launch(ctx, who);
     if (rc != PALSGD_OK) return rc;
     ctx->clip_armed = true;
     return PALSGD_OK;
+}
+
+static palsgd_status clip_norm_checks(palsgd_ctx* ctx, const char* who, float max_norm) {
+    if (!ctx) {
+        set_error(g_error, "%s: NULL context", who);
+        return PALSGD_EINVAL;
+    }
+    if (!(max_norm > 0.0f) || !std::isfinite(max_norm)) {
+        set_error(ctx->error, "%s: max_norm must be finite and > 0", who);
+        return PALSGD_EINVAL;
+    }
+    return PALSGD_OK;
+}
+
+palsgd_status palsgd_clip_grad_norm(palsgd_ctx* ctx, float max_norm, float* norms_out_dev, void* stream) {
+    palsgd_status rc = clip_norm_checks(ctx, "palsgd_clip_grad_norm", max_norm);
+    if (rc == PALSGD_OK) rc = begin_launches(ctx, "palsgd_clip_grad_norm");
+    if (rc != PALSGD_OK) return rc;
+    return clip_norm_launches(ctx, "palsgd_clip_grad_norm", max_norm, norms_out_dev, scratch_partials(ctx),
+                              scratch_fold(ctx), (hipStream_t)stream);
 }
 
 palsgd_status palsgd_clip_mean_grad_norm(palsgd_ctx* ctx, float max_norm, const float* grad_scale,
@@ -786,14 +865,15 @@ palsgd_status palsgd_clip_mean_grad_norm(palsgd_ctx* ctx, float max_norm, const 
         }
     a.inv_k = (float)(1.0 / (double)K);
     a.lr = a.c1 = a.c2 = 0.0f;
-    palsgd_status rc = ensure_scratch(ctx);
-    if (rc != PALSGD_OK) return rc;
+    palsgd_status rc;
     const uint64_t span = (uint64_t)kTile * kMeanTiles;
     const uint32_t parts = (uint32_t)((ctx->P_padded + span - 1) / span);
     const uint32_t gbytes = ctx->cfg.grad_dtype == PALSGD_GRAD_BF16 ? 2u : 4u;
     // a wavefront has at most eight row loads in flight at a time: size the cap on those
     const uint32_t lds = lds_cap(auto_waves(gbytes * (K < 8 ? K : 8u) * kTile, 4), 0);
     hipStream_t st = (hipStream_t)stream;
+    rc = begin_launches(ctx, "palsgd_clip_mean_grad_norm");
+    if (rc != PALSGD_OK) return rc;
     if (ctx->cfg.grad_dtype == PALSGD_GRAD_BF16)
         sumsq_mean_kernel<PALSGD_GRAD_BF16><<<parts, kWave, lds, st>>>(ctx->buf.G, a, scratch_partials(ctx),
                                                                       ctx->P_padded, ctx->buf.row_stride, K);
@@ -813,11 +893,12 @@ palsgd_status palsgd_diagnostics(palsgd_ctx* ctx, float* out_dev, void* stream) 
         set_error(ctx ? ctx->error : g_error, "palsgd_diagnostics: NULL argument");
         return PALSGD_EINVAL;
     }
-    palsgd_status rc = ensure_scratch(ctx);
-    if (rc != PALSGD_OK) return rc;
+    palsgd_status rc;
     const uint32_t K = ctx->cfg.K, n_part = diag_parts(ctx);
     const float inv_k = (float)(1.0 / (double)K);
     hipStream_t st = (hipStream_t)stream;
+    rc = begin_launches(ctx, "palsgd_diagnostics");
+    if (rc != PALSGD_OK) return rc;
     rc = end_warmup_sharing(ctx, "palsgd_diagnostics", st);  // the rows of X are read here
     if (rc != PALSGD_OK) return rc;
     diag_kernel<<<n_part, kWave, 0, st>>>(ctx->buf.X, ctx->buf.XG, scratch_partials(ctx), ctx->P_padded,
@@ -832,17 +913,14 @@ palsgd_status palsgd_capturable_begin(palsgd_ctx* ctx, uint64_t t0, void* stream
         set_error(g_error, "palsgd_capturable_begin: NULL context");
         return PALSGD_EINVAL;
     }
-    if (!ctx->d_schedule) {
-        hipError_t e = hipMalloc(&ctx->d_schedule, sizeof(DevSchedule));
-        if (e != hipSuccess) {
-            ctx->d_schedule = nullptr;
-            set_error(ctx->error, "hipMalloc(device schedule): %s", hipGetErrorString(e));
-            return PALSGD_ENOMEM;
-        }
+    if (ctx->capturable) {
+        set_error(ctx->error, "palsgd_capturable_begin: the schedule is already device-resident; call "
+                              "palsgd_capturable_end first");
+        return PALSGD_ESTATE;
     }
-    (void)lds_per_cu();
     {
-        palsgd_status rc = end_warmup_sharing(ctx, "palsgd_capturable_begin", (hipStream_t)stream);
+        palsgd_status rc = begin_launches(ctx, "palsgd_capturable_begin");
+        if (rc == PALSGD_OK) rc = end_warmup_sharing(ctx, "palsgd_capturable_begin", (hipStream_t)stream);
         if (rc != PALSGD_OK) return rc;
     }
     TauArgs a;
@@ -864,6 +942,10 @@ palsgd_status palsgd_step_capturable(palsgd_ctx* ctx, const float* alpha_eta_dev
         return PALSGD_ESTATE;
     }
     hipStream_t st = (hipStream_t)stream;
+    {
+        palsgd_status rc = begin_launches(ctx, "palsgd_step_capturable");
+        if (rc != PALSGD_OK) return rc;
+    }
     DevSchedule* ds = (DevSchedule*)ctx->d_schedule;
     PlanArgs a{ctx->cfg.seed, ctx->cfg.p, (double)ctx->cfg.beta1, (double)ctx->cfg.beta2, ctx->cfg.K,
                ctx->draw_threshold, ctx->cfg.inner == PALSGD_INNER_ADAMW ? 1u : 0u};
@@ -906,7 +988,14 @@ palsgd_status palsgd_get_state(const palsgd_ctx* ctx, uint64_t* tau, uint64_t* n
         return PALSGD_EINVAL;
     }
     if (ctx->capturable) {
-        set_error(g_error, "palsgd_get_state: the step counts are on the device; call palsgd_capturable_end first");
+        set_error(ctx->error, "palsgd_get_state: the step counts are on the device; call palsgd_capturable_end first");
+        return PALSGD_ESTATE;
+    }
+    if (ctx->moments_shared || ctx->model_shared) {
+        // what a checkpoint would save next to these counts is not there yet: rows 1..K-1 of M, V (and the rows of
+        // X after palsgd_ddp_step_shared) are stale until the warm-up's broadcast has run
+        set_error(ctx->error, "palsgd_get_state: DDP warm-up steps left the workers' rows shared; call "
+                              "palsgd_ddp_finish before saving state");
         return PALSGD_ESTATE;
     }
     if (tau) memcpy(tau, ctx->tau, ctx->cfg.K * sizeof(uint64_t));

@@ -47,6 +47,9 @@ def test_host_driven_calls_are_refused_while_device_resident():
         r.lib.palsgd_step_capturable(ae)
     assert e.value.status == 4
     r.lib.palsgd_capturable_begin(0)
+    with pytest.raises(PalsgdError) as e:                 # a second begin would overwrite the device's step counts
+        r.lib.palsgd_capturable_begin(5)
+    assert e.value.status == 4
     for call in (lambda: r.lib.palsgd_step(0, 1e-3, 16.0), lambda: r.lib.palsgd_inner_step(0, 1e-3),
                  lambda: r.lib.palsgd_pseudo_sync(0, 1e-3, 16.0), lambda: r.lib.palsgd_ddp_step(0, 1e-3),
                  lambda: r.lib.palsgd_get_state(), lambda: r.lib.palsgd_set_state([0, 0], 0)):
@@ -60,18 +63,18 @@ def test_host_driven_calls_are_refused_while_device_resident():
 
 @pytest.mark.parametrize("grad_dtype,clip", [("f32", None), ("bf16", None), ("f32", 20.0), ("bf16", 20.0)])
 def test_replayed_graph_of_a_window_follows_alg1(grad_dtype, clip):
-    """One captured window [H x (load gradients, (clip), local update), outer step] replayed for consecutive
-    windows: t, the draws and the step counts advance on the device, alpha changes between replays through the
-    device array, the clipping scales are recomputed on the device by every replay, and every replay is compared
-    with the oracle."""
+    """One captured window [H x (load gradients, (clip), local update), outer step with diagnostics] replayed for
+    consecutive windows: t, the draws and the step counts advance on the device, alpha changes between replays
+    through the device array, the clipping scales are recomputed on the device by every replay, and every
+    replay is compared with the oracle.  The clipping and diagnostics calls inside the capture are the first of
+    their kind on this context: nothing allocates after palsgd_init."""
     import oracle
     H, K = 3, 4
     r = _run(K=K, numels=RAGGED, grad_dtype=grad_dtype, p=0.3, H=H, seed=61, wd_mult=[1, 0, 1, 1, 0.5, 1, 0],
              **(dict(sigma=0.1, c_scale=0.25) if clip else dict(sigma=0.05)))
-    if clip:
-        r.lib.palsgd_clip_grad_norm(clip)                # allocates the reduction scratch: not inside a capture
     stage = torch.zeros((H,) + tuple(r.G.shape), dtype=r.G.dtype, device="cuda:0")
     ae = torch.tensor([r.alpha, r.eta], dtype=torch.float32, device="cuda:0")
+    diag = torch.zeros(2, dtype=torch.float32, device="cuda:0")
     r.lib.palsgd_capturable_begin(0)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
@@ -83,7 +86,7 @@ def test_replayed_graph_of_a_window_follows_alg1(grad_dtype, clip):
             if clip:
                 r.lib.palsgd_clip_grad_norm(clip)
             r.lib.palsgd_step_capturable(ae)
-        r.lib.palsgd_outer_step(0)
+        r.lib.palsgd_outer_step_diag(0, diag)
     torch.cuda.synchronize()
     clipped = False
     for w in range(5):
@@ -95,7 +98,11 @@ def test_replayed_graph_of_a_window_follows_alg1(grad_dtype, clip):
             if clip:
                 scales = np.array([oracle.clip_scale(v, float(np.float32(clip))) for v in r.ora.grad_norms()])
                 clipped = clipped or bool((scales < 1).any())
-            _, synced = r.ora.iteration(r.t, alpha, r.eta, grad_scale=scales)
+            r.ora.local_step(r.t, alpha, r.eta, grad_scale=scales)
+            synced = (r.t + 1) % H == 0
+            if synced:                                                 # the captured outer step reports these
+                want_diag = r.ora.diagnostics()
+                r.ora.outer_step()
             r.t += 1
         assert synced
         ae.copy_(torch.tensor([alpha, r.eta], dtype=torch.float32))
@@ -103,6 +110,7 @@ def test_replayed_graph_of_a_window_follows_alg1(grad_dtype, clip):
         g.replay()
         torch.cuda.synchronize()
         r.compare(check_state=False)
+        np.testing.assert_allclose(diag.cpu().numpy(), want_diag, rtol=2e-3, atol=1e-12)
         junk = torch.randn(1 << 18, device="cuda:0").sum().item()     # eager work between replays
     assert r.lib.palsgd_capturable_end() == r.t
     tau, _ = r.lib.palsgd_get_state()

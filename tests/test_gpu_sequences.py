@@ -21,7 +21,9 @@ def _run(**kw):
     return Run(**kw)
 
 
-def _identical_step_counts(r):
+def _identical_step_counts(r, shared):
+    if shared:                     # DDP steps need identical workers and keep them identical; the state call
+        return True                # itself is refused until the warm-up's broadcast has run
     tau, _ = r.lib.palsgd_get_state()
     return len(set(tau)) == 1
 
@@ -63,7 +65,7 @@ def test_random_call_sequence(seed):
                 r.lib.palsgd_set_tuning(int(rng.choice([0, 3, 8, 32])), int(rng.choice([0, 3, 4, 32])),
                                         int(rng.choice([0, 1, 2])))
             elif op in ("ddp", "ddp_shared", "clip_ddp"):
-                if not _identical_step_counts(r):               # the DDP step needs identical workers: refused, nothing changes
+                if not _identical_step_counts(r, shared):               # the DDP step needs identical workers: refused, nothing changes
                     with pytest.raises(PalsgdError) as e:
                         r.lib.palsgd_ddp_step(r.t, r.alpha)
                     assert e.value.status == 4
@@ -88,8 +90,13 @@ def test_random_call_sequence(seed):
                     r.lib.palsgd_outer_step_diag(t, out)
                     np.testing.assert_allclose(out.cpu().numpy(), want, rtol=2e-3, atol=1e-12)
             elif op == "state":                                 # step counts out and in again
-                tau, n_outer = r.lib.palsgd_get_state()
-                r.lib.palsgd_set_state(tau, n_outer)
+                if shared:                                      # refused while a warm-up's rows are still shared
+                    with pytest.raises(PalsgdError) as e:
+                        r.lib.palsgd_get_state()
+                    assert e.value.status == 4
+                else:
+                    tau, n_outer = r.lib.palsgd_get_state()
+                    r.lib.palsgd_set_state(tau, n_outer)
             elif op == "finish":
                 r.lib.palsgd_ddp_finish()
             elif op == "outer_lr":

@@ -71,9 +71,9 @@ def test_init_rejects_bad_arguments_without_touching_the_device():
         assert not out.value
         assert b"palsgd_init" in lib().palsgd_last_error(None)
     # a row longer than the launch grids can cover
-    cfg = make_config(2, [2 ** 38 + 1])
+    cfg = make_config(2, [2 ** 33 + 1])
     st, out = _init(cfg)
-    assert st == binding.PALSGD_EINVAL and not out.value and b"2^38" in lib().palsgd_last_error(None)
+    assert st == binding.PALSGD_EINVAL and not out.value and b"2^33" in lib().palsgd_last_error(None)
     # empty model and zero-sized tensor
     for numels in ([], [5, 0]):
         cfg = make_config(2, numels)
@@ -139,6 +139,36 @@ def test_state_roundtrip_and_step_argument_errors():
                      (lib().palsgd_outer_step, (None, 0, None)), (lib().palsgd_draw, (None, 0, None))):
         assert fn(*args) == binding.PALSGD_EINVAL
     lib().palsgd_destroy(None)
+
+
+def test_context_made_without_a_gpu_refuses_every_launch():
+    """With no GPU visible palsgd_init still hands out a context (for the draws and the scalar state above),
+    but nothing that would launch a kernel goes through: there is no CPU path."""
+    import torch
+    if torch.cuda.device_count() > 0:
+        pytest.skip("a GPU is visible: the context is a real one")
+    st, ctx = _init(make_config(3, [128], p=0.5))
+    assert st == 0
+    calls = [(lib().palsgd_step, (ctx, 0, 1e-3, 16.0, None, None, None)),
+             (lib().palsgd_inner_step, (ctx, 0, 1e-3, None, None, None)),
+             (lib().palsgd_pseudo_sync, (ctx, 0, 1e-3, 16.0, (C.c_uint8 * 3)(1, 1, 1), None)),
+             (lib().palsgd_step_sync, (ctx, 0, 1e-3, 16.0, None, None, None)),
+             (lib().palsgd_outer_step, (ctx, 0, None)), (lib().palsgd_outer_step_diag, (ctx, 0, FAKE, None)),
+             (lib().palsgd_ddp_step, (ctx, 0, 1e-3, None, None)), (lib().palsgd_ddp_step_shared, (ctx, 0, 1e-3, None, None)),
+             (lib().palsgd_ddp_finish, (ctx, None)), (lib().palsgd_clip_grad_norm, (ctx, 1.0, None, None)),
+             (lib().palsgd_clip_mean_grad_norm, (ctx, 1.0, None, None, None)), (lib().palsgd_diagnostics, (ctx, FAKE, None)),
+             (lib().palsgd_capturable_begin, (ctx, 0, None))]
+    for fn, args in calls:
+        assert fn(*args) == binding.PALSGD_EHIP, fn.__name__
+        assert b"no GPU" in lib().palsgd_last_error(ctx)
+    got, n = (C.c_uint64 * 3)(), C.c_uint64()
+    assert lib().palsgd_get_state(ctx, got, C.byref(n)) == 0 and list(got) == [0, 0, 0] and n.value == 0   # nothing advanced
+    lib().palsgd_destroy(ctx)
+    # an initial model cannot be copied anywhere either
+    cfg = make_config(3, [128])
+    out = C.c_void_p()
+    b = Buffers(X=FAKE, M=FAKE, V=FAKE, G=FAKE, XG=FAKE, OM=FAKE, row_stride=256)
+    assert lib().palsgd_init(C.byref(cfg), C.byref(b), FAKE, None, C.byref(out)) == binding.PALSGD_EHIP and not out.value
 
 
 def test_missing_library_fails_loudly(monkeypatch):
