@@ -58,13 +58,15 @@ def kernel_source_digest(csrc=None):
 
 
 def measured_traffic(workload_name):
+    """(counter bytes per launch, algorithmic bytes of the launches the counters saw), or (None, None) when the
+    counters were taken with another kernel source or workload."""
     try:
         digest = kernel_source_digest()
     except OSError:
-        return None
+        return None, None
     if digest != TRAFFIC["kernel_source_sha256"] or workload_name != TRAFFIC["workload"]:
-        return None
-    return TRAFFIC["bytes_per_launch"]
+        return None, None
+    return TRAFFIC["bytes_per_launch"], TRAFFIC["algorithmic_bytes_same_launches"]
 
 
 def grad_bytes_per_elem(inner: str, grad_dtype: str) -> int:
@@ -72,8 +74,8 @@ def grad_bytes_per_elem(inner: str, grad_dtype: str) -> int:
     return (24 if inner == "adamw" else 16) + g          # read+write x,m(,v) + read g
 
 
-def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=False, graph=False, wd_mult=None,
-            fused_sync=False, outer_adamw=False):
+def run_gpu(w, steps, warmup, reps, step_waves, outer_waves, outer_variant, extra=False, graph=False, wd_mult=None,
+            fused_sync=False):
     import torch
 
     from paper_2504_18454_amd import Palsgd, make_config, palsgd_layout
@@ -84,8 +86,7 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
         sys.exit("bench.py: no GPU is visible; the PALSGD update path runs in HIP kernels only (there is no CPU path)")
     dev = torch.device("cuda:0")
     cfg = make_config(w.K, w.numels, inner=w.inner, grad_dtype=w.grad_dtype, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
-                      weight_decay=w.weight_decay, momentum=w.momentum, p=w.p, H=w.H,
-                      outer_lr=1e-3 if outer_adamw else w.outer_lr, outer_opt="adamw" if outer_adamw else "sgd",
+                      weight_decay=w.weight_decay, momentum=w.momentum, p=w.p, H=w.H, outer_lr=w.outer_lr,
                       outer_momentum=w.outer_momentum, outer_nesterov=w.outer_nesterov, seed=w.seed, wd_mult=wd_mult)
     row, offs = palsgd_layout(cfg)
     K = w.K
@@ -121,8 +122,7 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     torch.cuda.synchronize()
     del cal_src, cal_dst
     stream = torch.cuda.Stream(device=dev)
-    OV = torch.empty(row, dtype=f, device=dev) if outer_adamw else None   # second moment of OuterOPT = AdamW
-    ctx = Palsgd(cfg, X, M, V, G, XG, OM, row, x0=x0, stream=stream, OV=OV)
+    ctx = Palsgd(cfg, X, M, V, G, XG, OM, row, x0=x0, stream=stream)
     if step_waves or outer_waves or outer_variant:
         ctx.palsgd_set_tuning(step_waves, outer_waves, outer_variant)
     torch.cuda.synchronize()
@@ -149,42 +149,93 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
     for t in range(warmup):
         one(t)
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
-    masks = [ctx.palsgd_draw(t) for t in range(warmup, warmup + steps)]
-    synced = []
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        synced.append(one(warmup + i, events[i]))
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
+    # `reps` timed windows of exactly `steps` consecutive steps of Alg. 1 each (t runs on from window to window, so
+    # synchronisation steps fall where (t+1) mod H = 0 puts them); the reported figure is the median window
     P = w.P
     gb, mb = grad_bytes_per_elem(w.inner, w.grad_dtype), 12
-    all_ms = [events[i][0].elapsed_time(events[i][1]) for i in range(steps)]
-    all_bytes = [float(P) * ((K - int(m.sum())) * gb + int(m.sum()) * mb) for m in masks]
-    plain = [i for i in range(steps) if not (fused_sync and synced[i])]      # launches of step_kernel
-    step_ms, step_bytes = [all_ms[i] for i in plain], [all_bytes[i] for i in plain]
-    outer_ms = [events[i][1].elapsed_time(events[i][2]) for i in range(steps) if synced[i]]
-    outer_bytes = float(P) * (8 * K + 16 + (8 if outer_adamw else 0))
-    total_bytes = sum(all_bytes) + outer_bytes * len(outer_ms)
-    fused_ms = [all_ms[i] for i in range(steps) if fused_sync and synced[i]]
+    outer_bytes = float(P) * (8 * K + 16)
+    windows, all_ms, all_bytes, outer_ms, fused_ms = [], [], [], [], []
+    t_next = warmup
+    for _ in range(reps):
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        masks = [ctx.palsgd_draw(t) for t in range(t_next, t_next + steps)]
+        synced = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            synced.append(one(t_next + i, events[i]))
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        t_next += steps
+        ms = [events[i][0].elapsed_time(events[i][1]) for i in range(steps)]
+        by = [float(P) * ((K - int(m.sum())) * gb + int(m.sum()) * mb) for m in masks]
+        n_sync = sum(synced)
+        for i in range(steps):
+            if fused_sync and synced[i]:
+                fused_ms.append(ms[i])
+            else:
+                all_ms.append(ms[i])
+                all_bytes.append(by[i])
+            if synced[i] and not fused_sync:
+                outer_ms.append(events[i][1].elapsed_time(events[i][2]))
+        windows.append(dict(elapsed=elapsed, n_outer=n_sync, bytes=sum(by) + outer_bytes * n_sync,
+                            mix=float(np.mean([m.mean() for m in masks]))))
+    order = sorted(range(reps), key=lambda r: windows[r]["elapsed"])
+    med = windows[order[len(order) // 2]]
+
+    # every kernel of the path alone, right after the windows, with events on the launch stream around each launch:
+    # the outer step (after an untimed local update, as in Alg. 1), the fused synchronisation step, and each branch
+    # of the local update with the branch forced for all K workers
+    def each(fn, n=6, before=None):
+        out = []
+        for _ in range(n + 1):
+            if before is not None:
+                before()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            fn()
+            b.record(stream)
+            torch.cuda.synchronize()
+            out.append(a.elapsed_time(b))
+        return out[1:]                                  # the first launch of a kernel is not counted
+
+    def kern(ms, bytes_per_elem):
+        m = float(np.median(ms))
+        gbps = float(P) * bytes_per_elem / m / 1e6
+        return dict(ms_per_launch=m, ms_min_max=[float(min(ms)), float(max(ms))], launches=len(ms), achieved=gbps,
+                    unit="GB/s", frac=gbps / HBM_PEAK_GBPS, bytes_per_elem=bytes_per_elem)
+
+    ones, zeros = np.ones(K, np.uint8), np.zeros(K, np.uint8)
+    local = lambda: ctx.palsgd_step(t_next, w.alpha, w.eta, None, None, stream)
+    alone_outer = each(lambda: ctx.palsgd_outer_step(t_next, stream), before=local)
+    alone_sync = each(lambda: ctx.palsgd_step_sync(t_next, w.alpha, w.eta, None, zeros, stream))
+    alone_grad = each(lambda: ctx.palsgd_inner_step(t_next, w.alpha, None, zeros, stream))
+    alone_mix = each(lambda: ctx.palsgd_pseudo_sync(t_next, w.alpha, w.eta, ones, stream)) if w.p > 0 else None
+    step_ms_mean = float(np.mean(all_ms))
+    outer_med = float(np.median(outer_ms + alone_outer))
+    bytes_mean = float(np.mean(all_bytes))
     res = dict(
-        elapsed=elapsed, updates=float(K) * P * steps, row=row,
-        step_kernel_ms_spread=[float(np.percentile(step_ms, q)) for q in (0, 10, 50, 90, 100)],
-        step_kernel_ms=float(np.mean(step_ms)), step_kernel_gbps=sum(step_bytes) / (sum(step_ms) * 1e-3) / 1e9,
-        step_kernel_bytes=float(np.mean(step_bytes)),
-        outer_kernel_ms=float(np.mean(outer_ms)) if outer_ms else None,
-        outer_kernel_gbps=(outer_bytes / (np.mean(outer_ms) * 1e-3) / 1e9) if outer_ms else None,
-        n_outer=len(outer_ms), mix_fraction=float(np.mean([m.mean() for m in masks])),
-        fused_sync_ms=float(np.mean(fused_ms)) if fused_ms else None,
-        blended_gbps=total_bytes / elapsed / 1e9,
+        elapsed=med["elapsed"], updates=float(K) * P * steps, row=row, reps=reps,
+        window_ms_per_step=[windows[r]["elapsed"] / steps * 1e3 for r in order],
+        window_outer_steps=[windows[r]["n_outer"] for r in order],
+        n_outer=med["n_outer"], mix_fraction=med["mix"], blended_gbps=med["bytes"] / med["elapsed"] / 1e9,
+        step_kernel_ms_spread=[float(np.percentile(all_ms, q)) for q in (0, 10, 50, 90, 100)],
+        step_kernel_ms=step_ms_mean, step_kernel_gbps=sum(all_bytes) / (sum(all_ms) * 1e-3) / 1e9,
+        step_kernel_bytes=bytes_mean, step_kernel_launches=len(all_ms),
+        outer=kern(outer_ms + alone_outer, 8 * K + 16), outer_in_windows=len(outer_ms),
+        sync_step=kern(alone_sync + fused_ms, K * (gb - 4) + 16 + 4 * K),
+        grad_only=kern(alone_grad, K * gb), mix_only=kern(alone_mix, K * mb) if alone_mix else None,
+        # one step of Alg. 1 with the synchronisation step's share: kernel time from the events, bytes from the
+        # timed launches' own branch mix
+        amortised_ms=step_ms_mean + outer_med / w.H,
+        amortised_gbps=(bytes_mean + outer_bytes / w.H) / ((step_ms_mean + outer_med / w.H) * 1e-3) / 1e9,
     )
+    t_after = t_next + 1
     torch.cuda.synchronize()
     if graph:
         # the same steps through the device-resident schedule, one captured window of H steps + outer step replayed
         ae = torch.tensor([w.alpha, w.eta], dtype=f, device=dev)
-        ctx.palsgd_capturable_begin(warmup + steps, stream)
+        ctx.palsgd_capturable_begin(t_after, stream)
         torch.cuda.synchronize()
         gr = torch.cuda.CUDAGraph()
         with torch.cuda.graph(gr, stream=stream):
@@ -192,29 +243,29 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
                 ctx.palsgd_step_capturable(ae)
             ctx.palsgd_outer_step(0)
         torch.cuda.synchronize()
-        windows = max(1, steps // w.H)
+        n_win = max(1, steps // w.H)
         gr.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(windows):
+        for _ in range(n_win):
             gr.replay()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         ctx.palsgd_capturable_end(stream)
-        res["graph"] = dict(windows=windows, ms_per_step=dt / (windows * w.H) * 1e3,
-                            value=float(K) * P * windows * w.H / dt)
+        res["graph"] = dict(windows=n_win, ms_per_step=dt / (n_win * w.H) * 1e3,
+                            value=float(K) * P * n_win * w.H / dt)
     if extra:
         # the kernels next to the hot path, each timed alone with events on the launch stream
-        def timed(fn, reps=10):
+        def timed(fn, n=10):
             fn()
             torch.cuda.synchronize()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record(stream)
-            for _ in range(reps):
+            for _ in range(n):
                 fn()
             b.record(stream)
             torch.cuda.synchronize()
-            return a.elapsed_time(b) / reps
+            return a.elapsed_time(b) / n
         gB = 4 if w.grad_dtype == "f32" else 2
         state = 12 if w.inner == "adamw" else 8
         out2 = torch.empty(2, dtype=f, device=dev)
@@ -225,13 +276,6 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
         res["clip_mean_grad_norm"] = dict(ms=ms, gbps=float(P) * K * gB / ms / 1e6, bytes_per_elem=K * gB)
         ms = timed(lambda: ctx.palsgd_diagnostics(out2, stream))
         res["diagnostics"] = dict(ms=ms, gbps=float(P) * (4 * K + 4) / ms / 1e6, bytes_per_elem=4 * K + 4)
-        ones, zeros = np.ones(K, np.uint8), np.zeros(K, np.uint8)
-        gb_ = grad_bytes_per_elem(w.inner, w.grad_dtype)
-        ms = timed(lambda: ctx.palsgd_inner_step(0, w.alpha, None, zeros, stream))
-        res["gradient_branch_only"] = dict(ms=ms, gbps=float(P) * K * gb_ / ms / 1e6, bytes_per_elem=gb_)
-        if w.p > 0:
-            ms = timed(lambda: ctx.palsgd_pseudo_sync(0, w.alpha, w.eta, ones, stream))
-            res["mixing_branch_only"] = dict(ms=ms, gbps=float(P) * K * 12 / ms / 1e6, bytes_per_elem=12)
         ctx.palsgd_outer_step(0, stream)                # workers identical again, as the DDP step requires
         tau0 = max(ctx.palsgd_get_state()[0])
         ctx.palsgd_set_state([tau0] * K, ctx.palsgd_get_state()[1])
@@ -243,6 +287,16 @@ def run_gpu(w, steps, warmup, step_waves, outer_waves, outer_variant, extra=Fals
         res["ddp_step_shared"] = dict(ms=ms, gbps=float(P) * ddp_s / ms / 1e6, bytes_per_elem=ddp_s)
     ctx.palsgd_destroy()
     return res
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return None
 
 
 def run_cpu_baseline(w, slice_div=2, threads=None):
@@ -276,16 +330,12 @@ def run_cpu_baseline(w, slice_div=2, threads=None):
                        f"{steps} steps incl. one outer step, {dt:.1f} s")
 
 
-def K_bytes(w):
-    """Algorithmic bytes per element of a fused synchronisation step with every replica on the gradient branch."""
-    return w.K * (grad_bytes_per_elem(w.inner, w.grad_dtype) - 4) + 16 + 4 * w.K
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--reps", type=int, default=5, help="timed windows of --steps steps each; the median one is reported")
     ap.add_argument("--workload", default="gptneo125m_k8")
     ap.add_argument("--step-waves", type=int, default=0, help="resident wavefronts per CU, local update (0 = library's choice)")
     ap.add_argument("--outer-waves", type=int, default=0, help="resident wavefronts per CU, outer step (0 = library's choice)")
@@ -293,8 +343,6 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decay-1d", action="store_true",
                     help="weight-decay multiplier 0 on one-dimensional tensors (biases, norms): exercises the per-tensor table")
-    ap.add_argument("--outer-adamw", action="store_true",
-                    help="OuterOPT = AdamW (outer lr 1e-3) instead of the workload's Nesterov momentum")
     ap.add_argument("--fused-sync", action="store_true",
                     help="synchronisation steps as ONE launch (palsgd_step_sync) instead of palsgd_step + palsgd_outer_step")
     ap.add_argument("--graph", action="store_true",
@@ -306,10 +354,13 @@ def main():
         print("bench.py: this build runs on ONE GPU (K replicas share it); --gpus must be 1. "
               "No multi-GPU figure exists for it.", file=sys.stderr)
         sys.exit(2)
+    if a.reps < 1 or a.steps < 1:
+        sys.exit("bench.py: --steps and --reps must be >= 1")
     from paper_2504_18454_amd.workloads import workload
     w = workload(a.workload)
     wd_mult = [0.0 if len(shape) == 1 else 1.0 for _, shape in w.tensors] if a.no_decay_1d else None
-    r = run_gpu(w, a.steps, a.warmup, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph, wd_mult, a.fused_sync, a.outer_adamw)
+    r = run_gpu(w, a.steps, a.warmup, a.reps, a.step_waves, a.outer_waves, a.outer_variant, a.extra_kernels, a.graph,
+                wd_mult, a.fused_sync)
     cpu = None
     if not a.no_cpu_baseline:
         # bounded sample: about K * 62M * (H+1) element updates for the all-threads leg whatever the workload
@@ -320,39 +371,51 @@ def main():
             div *= 2
         cpu = run_cpu_baseline(w, slice_div=div)
         one = run_cpu_baseline(w, slice_div=32 * div, threads=1)  # the same loop on one core, smaller slice
+        cpu["cpu_model"] = cpu_model()
         cpu["one_core"] = {"value": one["value"], "sample": one["sample"]}
         cpu["gpu_over_cpu"] = r["updates"] / r["elapsed"] / cpu["value"]       # context only: the roofline fraction is the measure
     gb = grad_bytes_per_elem(w.inner, w.grad_dtype)
+    traffic, traffic_alg = measured_traffic(a.workload)
     out = {
         "metric": "replica-param updates/s", "value": r["updates"] / r["elapsed"], "unit": "replica-param updates/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": r["elapsed"] / a.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": a.workload, "K": w.K, "P": w.P, "tensors": len(w.tensors), "inner": w.inner,
                    "grad_dtype": w.grad_dtype, "p": w.p, "H": w.H, "eta": w.eta, "alpha": w.alpha,
-                   "outer": "adamw lr 0.001" if a.outer_adamw else f"nesterov lr {w.outer_lr} mu {w.outer_momentum}", "outer_steps_timed": r["n_outer"],
+                   "outer": f"nesterov lr {w.outer_lr} mu {w.outer_momentum}", "outer_steps_timed": r["n_outer"],
                    "mix_fraction_timed": round(r["mix_fraction"], 4),
                    "weight_decay": "uniform" if not a.no_decay_1d else "per tensor: 0 on 1-D tensors"},
+        # value and ms_per_step are the MEDIAN of `reps` timed windows of `steps` steps each (sorted list beside it)
+        "reps": r["reps"], "ms_per_step_of_each_window_sorted": r["window_ms_per_step"],
+        "outer_steps_in_each_window_sorted": r["window_outer_steps"],
         "hbm_GBps_whole_step": r["blended_gbps"], "hbm_frac_whole_step": r["blended_gbps"] / HBM_PEAK_GBPS,
+        # one step of Alg. 1 with 1/H of a synchronisation step's outer launch, from kernel event times
+        "step_with_outer_share": {"ms": r["amortised_ms"], "achieved": r["amortised_gbps"], "unit": "GB/s",
+                                  "frac": r["amortised_gbps"] / HBM_PEAK_GBPS},
         "roofline": {"bound": "hbm", "kernel": "step_kernel", "achieved": r["step_kernel_gbps"],
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": r["step_kernel_gbps"] / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic(a.workload), "bytes_per_launch": r["step_kernel_bytes"], "ms_per_launch": r["step_kernel_ms"],
+                     # counter bytes per launch of the counter runs, the algorithmic bytes of those same launches, their
+                     # ratio (the launches timed here have their own branch mix, hence their own bytes_per_launch)
+                     "traffic": traffic, "traffic_algorithmic_same_launches": traffic_alg,
+                     "traffic_ratio": (traffic / traffic_alg) if traffic else None,
+                     "bytes_per_launch": r["step_kernel_bytes"], "ms_per_launch": r["step_kernel_ms"],
+                     "launches": r["step_kernel_launches"],
                      "ms_per_launch_min_p10_p50_p90_max": r["step_kernel_ms_spread"],
                      "bytes_per_elem": {"grad": gb, "mix": 12}},
-        "outer_kernel": {"ms_per_launch": r["outer_kernel_ms"], "achieved": r["outer_kernel_gbps"], "unit": "GB/s",
-                         "frac": (r["outer_kernel_gbps"] / HBM_PEAK_GBPS) if r["outer_kernel_gbps"] else None,
-                         "bytes_per_elem": 8 * w.K + 16 + (8 if a.outer_adamw else 0)},
+        # the outer step (outer_kernel_walk): launches inside the windows plus six timed alone right after them
+        "outer_kernel": dict(r["outer"], launches_in_windows=r["outer_in_windows"]),
+        # each kernel of the path alone (median of six launches, HIP events on the launch stream)
+        "branch_kernels": {"gradient_branch_only": r["grad_only"], "mixing_branch_only": r["mix_only"],
+                           "fused_sync_step": r["sync_step"]},
         "cpu_baseline": cpu,
     }
     if a.fused_sync:
         out["config"]["sync_steps"] = "fused (palsgd_step_sync)"
-        out["outer_kernel"] = None
-        out["sync_step_kernel"] = {"ms_per_launch": r["fused_sync_ms"],
-                                   "bytes_per_elem_all_gradient": K_bytes(w), "unit": "ms"}
     if a.graph:
         out["hip_graph_replay"] = r["graph"]
     if a.extra_kernels:
-        out["extra_kernels"] = {k: r[k] for k in ("gradient_branch_only", "mixing_branch_only", "ddp_step", "ddp_step_shared",
-                                                  "clip_grad_norm", "clip_mean_grad_norm", "diagnostics") if k in r}
+        out["extra_kernels"] = {k: r[k] for k in ("ddp_step", "ddp_step_shared", "clip_grad_norm", "clip_mean_grad_norm",
+                                                  "diagnostics") if k in r}
     print(json.dumps(out))
 
 

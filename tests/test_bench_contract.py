@@ -18,8 +18,15 @@ def test_algorithmic_bytes_and_traffic_key():
     assert bench.grad_bytes_per_elem("sgdm", "f32") == 20 and bench.grad_bytes_per_elem("sgdm", "bf16") == 18
     # the counter-derived traffic is reported only for the kernel source it was measured with
     same = bench.kernel_source_digest() == bench.TRAFFIC["kernel_source_sha256"]
-    got = bench.measured_traffic("gptneo125m_k8")
-    assert (got == bench.TRAFFIC["bytes_per_launch"]) if same else (got is None)
-    assert bench.measured_traffic("resnet50_k8") is None
-    if got is not None:
-        assert abs(got / bench.TRAFFIC["algorithmic_bytes_same_launches"] - 1) < 0.01
+    got, alg = bench.measured_traffic("gptneo125m_k8")
+    assert (got == bench.TRAFFIC["bytes_per_launch"]) if same else (got is None and alg is None)
+    assert bench.measured_traffic("resnet50_k8") == (None, None)
+    if got is not None:                                 # reported next to the algorithmic bytes of the SAME launches
+        assert alg == bench.TRAFFIC["algorithmic_bytes_same_launches"] and abs(got / alg - 1) < 0.01
+
+
+def test_cpu_model_is_a_string_here():
+    sys.path.insert(0, ROOT)
+    import bench
+    m = bench.cpu_model()
+    assert m is None or (isinstance(m, str) and m)
