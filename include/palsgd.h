@@ -225,6 +225,19 @@ palsgd_status palsgd_ddp_finish(palsgd_ctx *ctx, void *stream);
  * EINVAL unless max_norm is finite and > 0. */
 palsgd_status palsgd_clip_grad_norm(palsgd_ctx *ctx, float max_norm, float *norms_out_dev, void *stream);
 
+/* palsgd_clip_grad_norm for callers that cannot allocate or may not touch allocated scratch: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results (the
+ * same kernels, bit for bit) and the same arming of the next gradient step; the partial sums go through a
+ * fixed array that is part of the library's code object (16.1 MiB on every GPU the library runs on, held
+ * until the process ends) instead of the context's reduction scratch, and the call allocates and frees
+ * nothing, on the host or on the device.  palsgd_init looks the array's device address up once per device.
+ * Limit: K * ceil(P_padded / 4096) <= 2^22 partial sums (K * P_padded up to 1.7e10 elements); EINVAL with
+ * the two numbers in the error text beyond that, before any launch.
+ * All contexts on one GPU share the array and it keeps the last call's contents (none of which a later call
+ * reads before writing): two calls that overlap in time on one GPU, from different streams or contexts,
+ * race on it and may both return wrong norms.  The scales themselves land in the context's own memory. */
+palsgd_status palsgd_clip_grad_norm_noalloc(palsgd_ctx *ctx, float max_norm, float *norms_out_dev, void *stream);
+
 /* Clipping in the DDP phase, where the optimizer sees the averaged gradient (Sec. 3.1):
  * norm = |(1/K) sum_k grad_scale[k] G[k]|_2 and scale = min(1, max_norm / (norm + 1e-6))
  * stay on the device; the next palsgd_ddp_step multiplies the averaged gradient by scale

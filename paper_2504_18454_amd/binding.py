@@ -28,7 +28,7 @@ EXPORTS = ("palsgd_layout", "palsgd_init", "palsgd_draw", "palsgd_inner_step", "
            "palsgd_last_error", "palsgd_destroy", "palsgd_set_tuning", "palsgd_ddp_step",
            "palsgd_clip_grad_norm", "palsgd_diagnostics", "palsgd_outer_step_diag", "palsgd_capturable_begin",
            "palsgd_step_capturable", "palsgd_capturable_end", "palsgd_ddp_finish", "palsgd_clip_mean_grad_norm", "palsgd_step_sync",
-           "palsgd_ddp_step_shared", "palsgd_set_outer_lr")
+           "palsgd_ddp_step_shared", "palsgd_set_outer_lr", "palsgd_clip_grad_norm_noalloc")
 
 
 class PalsgdError(RuntimeError):
@@ -91,6 +91,8 @@ def lib() -> C.CDLL:
         L.palsgd_ddp_finish.argtypes = [vp, vp]
         L.palsgd_clip_grad_norm.restype = st
         L.palsgd_clip_grad_norm.argtypes = [vp, f, vp, vp]
+        L.palsgd_clip_grad_norm_noalloc.restype = st
+        L.palsgd_clip_grad_norm_noalloc.argtypes = [vp, f, vp, vp]
         L.palsgd_clip_mean_grad_norm.restype = st
         L.palsgd_clip_mean_grad_norm.argtypes = [vp, f, C.POINTER(f), vp, vp]
         L.palsgd_diagnostics.restype = st
@@ -284,6 +286,11 @@ class Palsgd:
         """norms_out: torch CUDA float32 tensor of K elements (or a device address), or None."""
         ptr = _dev_f32(norms_out, self.K, "norms_out")
         _check(lib().palsgd_clip_grad_norm(self._ctx, max_norm, ptr, _stream_handle(stream)), self._ctx)
+
+    def palsgd_clip_grad_norm_noalloc(self, max_norm, norms_out=None, stream=None):
+        """As palsgd_clip_grad_norm, through the library's static scratch (no allocation anywhere)."""
+        ptr = _dev_f32(norms_out, self.K, "norms_out")
+        _check(lib().palsgd_clip_grad_norm_noalloc(self._ctx, max_norm, ptr, _stream_handle(stream)), self._ctx)
 
     def palsgd_clip_mean_grad_norm(self, max_norm, grad_scale=None, norm_out=None, stream=None):
         """norm_out: torch CUDA float32 tensor of 1 element (or a device address), or None."""

@@ -47,6 +47,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -59,6 +60,16 @@
 #include "warmup_kernels.h"
 
 using namespace palsgd_dev;
+
+// Scratch of palsgd_clip_grad_norm_noalloc, the entry point for callers that cannot allocate: part of the
+// library's code object, so every GPU the library runs on holds its own copy (16.1 MiB) until the process
+// ends.  Layout: 2 * PALSGD_MAX_K * kFold floats that hold the second-stage sums (as PALSGD_MAX_K * kFold
+// doubles), then up to kStaticMaxParts first-stage partial sums.  In host code this name is only a handle
+// for hipGetSymbolAddress: the device address it yields (per device, kept in g_static_scratch) is what the
+// launches get.
+constexpr uint32_t kStaticFoldFloats = 2u * PALSGD_MAX_K * kFold;
+constexpr uint32_t kStaticMaxParts = 1u << 22;
+static __device__ __align__(256) float scratch[kStaticFoldFloats + kStaticMaxParts];
 
 namespace {
 
@@ -74,6 +85,33 @@ void set_error(char* dst, const char* fmt, ...) {
 }
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Device address of `scratch` on the current device, looked up once per device (with that device current)
+// and kept: each GPU has its own copy of the array at its own address.
+constexpr int kMaxDevices = 64;
+float* g_static_scratch[kMaxDevices] = {nullptr};
+std::mutex g_static_scratch_mutex;
+
+palsgd_status static_scratch(char* err, float** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        set_error(err, "static scratch: hipGetDevice: %s (device %d)", hipGetErrorString(e), dev);
+        return PALSGD_EHIP;
+    }
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_error(err, "static scratch: hipGetSymbolAddress on device %d: %s", dev, hipGetErrorString(e));
+            return PALSGD_EHIP;
+        }
+        g_static_scratch[dev] = (float*)p;
+    }
+    if (out) *out = g_static_scratch[dev];
+    return PALSGD_OK;
+}
 
 }  // namespace
 
@@ -560,6 +598,7 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
     } else {
         rc = c->wd_uniform ? PALSGD_OK : build_wd_table(c);
         if (rc == PALSGD_OK) rc = alloc_device_state(c);
+        if (rc == PALSGD_OK) rc = static_scratch(c->error, nullptr);  // set-up of palsgd_clip_grad_norm_noalloc
         if (rc != PALSGD_OK) {
             memcpy(g_error, c->error, sizeof g_error);
             palsgd_destroy(c);
@@ -802,7 +841,7 @@ palsgd_status palsgd_ddp_finish(palsgd_ctx* ctx, void* stream) {
     return rc != PALSGD_OK ? rc : end_warmup_sharing(ctx, "palsgd_ddp_finish", (hipStream_t)stream);
 }
 
-// Body of palsgd_clip_grad_norm: `partial` holds K * norm_parts floats
+// Shared body of palsgd_clip_grad_norm and palsgd_clip_grad_norm_noalloc: `partial` holds K * norm_parts floats
 // and `fold` K * kFold doubles; the scales go to the context's own memory in both cases.
 static palsgd_status clip_norm_launches(palsgd_ctx* ctx, const char* who, float max_norm, float* norms_out_dev,
                                         float* partial, double* fold, hipStream_t st) {
@@ -840,6 +879,26 @@ palsgd_status palsgd_clip_grad_norm(palsgd_ctx* ctx, float max_norm, float* norm
     if (rc != PALSGD_OK) return rc;
     return clip_norm_launches(ctx, "palsgd_clip_grad_norm", max_norm, norms_out_dev, scratch_partials(ctx),
                               scratch_fold(ctx), (hipStream_t)stream);
+}
+
+palsgd_status palsgd_clip_grad_norm_noalloc(palsgd_ctx* ctx, float max_norm, float* norms_out_dev, void* stream) {
+    const char* who = "palsgd_clip_grad_norm_noalloc";
+    palsgd_status rc = clip_norm_checks(ctx, who, max_norm);
+    if (rc != PALSGD_OK) return rc;
+    const uint64_t parts = (uint64_t)ctx->cfg.K * norm_parts(ctx);
+    if (parts > kStaticMaxParts) {
+        set_error(ctx->error, "%s: K * ceil(P_padded / %d) = %llu partial sums, the static scratch holds %u; use "
+                              "palsgd_clip_grad_norm", who, kTile * kNormTiles, (unsigned long long)parts, kStaticMaxParts);
+        return PALSGD_EINVAL;
+    }
+    rc = begin_launches(ctx, who);
+    if (rc != PALSGD_OK) return rc;
+    float* base = nullptr;  // the array's device address on the current device, never the array's name
+    rc = static_scratch(ctx->error, &base);
+    if (rc != PALSGD_OK) return rc;
+    // nothing needs clearing: the launches overwrite every partial sum and every second-stage sum they read
+    return clip_norm_launches(ctx, who, max_norm, norms_out_dev, base + kStaticFoldFloats, (double*)base,
+                              (hipStream_t)stream);
 }
 
 palsgd_status palsgd_clip_mean_grad_norm(palsgd_ctx* ctx, float max_norm, const float* grad_scale,
