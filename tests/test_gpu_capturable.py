@@ -61,8 +61,9 @@ def test_host_driven_calls_are_refused_while_device_resident():
     r.close()
 
 
-@pytest.mark.parametrize("grad_dtype,clip", [("f32", None), ("bf16", None), ("f32", 20.0), ("bf16", 20.0)])
-def test_replayed_graph_of_a_window_follows_alg1(grad_dtype, clip):
+@pytest.mark.parametrize("grad_dtype,clip,unit_scale", [("f32", None, False), ("bf16", None, False), ("f32", 20.0, False),
+                                                        ("bf16", 20.0, False), ("f32", 50.0, True), ("bf16", 50.0, True)])
+def test_replayed_graph_of_a_window_follows_alg1(grad_dtype, clip, unit_scale):
     """One captured window [H x (load gradients, (clip), local update), outer step with diagnostics] replayed for
     consecutive windows: t, the draws and the step counts advance on the device, alpha changes between replays
     through the device array, the clipping scales are recomputed on the device by every replay, and every
@@ -71,7 +72,8 @@ def test_replayed_graph_of_a_window_follows_alg1(grad_dtype, clip):
     import oracle
     H, K = 3, 4
     r = _run(K=K, numels=RAGGED, grad_dtype=grad_dtype, p=0.3, H=H, seed=61, wd_mult=[1, 0, 1, 1, 0.5, 1, 0],
-             **(dict(sigma=0.1, c_scale=0.25) if clip else dict(sigma=0.05)))
+             **(dict(sigma=0.5, c_scale=1.0, moment_floor_by_gradient=True) if unit_scale
+                else dict(sigma=0.1, c_scale=0.25) if clip else dict(sigma=0.05)))
     stage = torch.zeros((H,) + tuple(r.G.shape), dtype=r.G.dtype, device="cuda:0")
     ae = torch.tensor([r.alpha, r.eta], dtype=torch.float32, device="cuda:0")
     diag = torch.zeros(2, dtype=torch.float32, device="cuda:0")
@@ -98,6 +100,7 @@ def test_replayed_graph_of_a_window_follows_alg1(grad_dtype, clip):
             if clip:
                 scales = np.array([oracle.clip_scale(v, float(np.float32(clip))) for v in r.ora.grad_norms()])
                 clipped = clipped or bool((scales < 1).any())
+            r.note_gradients(scales)
             r.ora.local_step(r.t, alpha, r.eta, grad_scale=scales)
             synced = (r.t + 1) % H == 0
             if synced:                                                 # the captured outer step reports these

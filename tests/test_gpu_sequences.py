@@ -36,8 +36,11 @@ def test_random_call_sequence(seed):
     K = int(rng.choice([1, 2, 3, 5, 8]))
     inner, grad_dtype = [("adamw", "f32"), ("adamw", "bf16"), ("sgdm", "f32"), ("sgdm", "bf16")][seed % 4]
     outer_adamw = seed % 5 == 2
+    # odd seeds at the benchmark configurations' gradient scale (first moment compared with its floor in units of
+    # the largest scaled gradient), even seeds at a quarter of it (fixed floor everywhere)
+    scale = dict(sigma=0.5, c_scale=1.0, moment_floor_by_gradient=True) if seed % 2 else dict(sigma=0.1, c_scale=0.25)
     r = _run(K=K, numels=NUMELS, inner=inner, grad_dtype=grad_dtype, p=0.3, H=int(rng.choice([2, 3, 5])), seed=70 + seed,
-             sigma=0.1, c_scale=0.25, wd_mult=[1, 0, 1, 0.5, 1] if seed % 2 else None, row_extra=seed % 2,
+             **scale, wd_mult=[1, 0, 1, 0.5, 1] if seed % 2 else None, row_extra=seed % 2,
              inner_nesterov=bool(seed % 3 == 0),
              **(dict(outer_opt="adamw", outer_lr=0.02, outer_beta1=0.8, outer_beta2=0.95, outer_eps=0.05, outer_weight_decay=0.05)
                 if outer_adamw else {}))
@@ -111,6 +114,7 @@ def test_random_call_sequence(seed):
                 for _ in range(int(rng.integers(1, 4))):
                     t = r.t
                     r.make_gradients()
+                    r.note_gradients(None)
                     _, synced = r.ora.iteration(t, r.alpha, r.eta)
                     r.lib.palsgd_step_capturable(ae)
                     if synced:

@@ -141,6 +141,25 @@ def test_state_roundtrip_and_step_argument_errors():
     lib().palsgd_destroy(None)
 
 
+def test_norm_of_a_periodic_row_from_one_period(oracle_mod):
+    """The every-element GPU tests take the norm of a full-size row whose content repeats with period B from
+    one period: sum_j count[j] g[j]^2.  Here the same row is written out and handed to the checker's norm."""
+    from parity import periodic_counts
+    numels, B = [1000, 64, 3, 777, 130], 256
+    offs, row = flat_layout(numels)
+    count = periodic_counts(numels, offs, B)
+    rng = np.random.default_rng(5)
+    block = rng.standard_normal(B).astype(np.float32)
+    full = np.zeros(row, np.float32)
+    for o, n in zip(offs, numels):
+        idx = np.arange(o, o + n)
+        full[idx] = block[idx % B]
+    assert count.sum() == sum(numels)
+    want = oracle_mod.grad_norm(full)
+    got = float(np.sqrt((block.astype(np.float64) ** 2 * count).sum()))
+    assert got == pytest.approx(want, rel=1e-12)
+
+
 def test_context_made_without_a_gpu_refuses_every_launch():
     """With no GPU visible palsgd_init still hands out a context (for the draws and the scalar state above),
     but nothing that would launch a kernel goes through: there is no CPU path."""
