@@ -187,7 +187,9 @@ def run_gpu(w, steps, warmup, reps, step_waves, outer_waves, outer_variant, extr
     # the outer step (after an untimed local update, as in Alg. 1), the fused synchronisation step, and each branch
     # of the local update with the branch forced for all K workers
     def each(fn, n=6, before=None):
-        out = []
+        # all launches are enqueued without a host wait in between, so the device is still busy with the previous
+        # one while the host prepares the next and the events bracket kernel time, not host latency
+        pairs = []
         for _ in range(n + 1):
             if before is not None:
                 before()
@@ -195,9 +197,9 @@ def run_gpu(w, steps, warmup, reps, step_waves, outer_waves, outer_variant, extr
             a.record(stream)
             fn()
             b.record(stream)
-            torch.cuda.synchronize()
-            out.append(a.elapsed_time(b))
-        return out[1:]                                  # the first launch of a kernel is not counted
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in pairs[1:]]   # the first launch of a kernel is not counted
 
     def kern(ms, bytes_per_elem):
         m = float(np.median(ms))

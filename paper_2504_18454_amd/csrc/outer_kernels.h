@@ -33,12 +33,13 @@ __device__ __forceinline__ f4 outer4(f4 dsum, f4 xg, f4& om, f4& ov, const Outer
 }
 
 // Variant 1: one wavefront per tile; each lane owns four consecutive elements and walks the
-// K rows in ascending order, eight independent loads in flight at a time.
+// K rows in ascending order, KU independent loads in flight at a time (8; 16 from K = 32 up, where
+// halving the number of load rounds per wavefront is worth 3 %).
 // DIAG: also leaves, per wavefront, the partial sums of sum_k |x - x_k|^2 and |Delta|^2
 // (App. A.3) taken from the values already in registers: no extra HBM reads.
 // OADAM: OuterOPT = AdamW (a compile-time switch: as a run-time one it slowed the SGD-family
 // outer step by a quarter).
-template <bool DIAG, bool OADAM>
+template <bool DIAG, bool OADAM, int KU>
 __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X, float* __restrict__ XG,
                                                            float* __restrict__ OM, float* __restrict__ OV, uint64_t n,
                                                            uint64_t row_stride, uint32_t K, OuterArgs a,
@@ -50,13 +51,13 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
         f4 xg = ld4(XG + e);
         f4 om = ld4(OM + e), ov;
         if (OADAM) ov = ld4(OV + e);
-        for (uint32_t k0 = 0; k0 < K; k0 += 8) {
-            f4 t[8];
+        for (uint32_t k0 = 0; k0 < K; k0 += KU) {
+            f4 t[KU];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < KU; ++u)
                 if (k0 + u < K) t[u] = ld4(X + (uint64_t)(k0 + u) * row_stride + e);
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < KU; ++u)
                 if (k0 + u < K) {
                     f4 d = xg - t[u];
                     sum += d;

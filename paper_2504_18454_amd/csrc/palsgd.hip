@@ -694,8 +694,10 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
     const uint64_t n = ctx->P_padded;
     hipStream_t st = (hipStream_t)stream;
     const uint32_t variant = ctx->outer_variant ? ctx->outer_variant : 1u;
-    const uint32_t waves = ctx->outer_waves ? ctx->outer_waves
-                                            : auto_waves((8u * K + 16u) * kTile, 4);  // rows go 8 at a time: 4 is best from K=16 up
+    // Rows go 8 at a time and 4 resident wavefronts per CU are best from K = 16 up; from K = 32 up 16 at a time
+    // and 3 wavefronts (sweeps of both, K = 4 .. 64).
+    const bool deep = K >= 32;
+    const uint32_t waves = ctx->outer_waves ? ctx->outer_waves : (deep ? 3u : auto_waves((8u * K + 16u) * kTile, 4));
     const palsgd_buffers& b = ctx->buf;
     const bool oadam = ctx->cfg.outer_opt == PALSGD_OUTER_ADAMW;
     {
@@ -704,14 +706,18 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
         if (rc == PALSGD_OK) rc = end_warmup_sharing(ctx, who, st);  // the rows of X are read here
         if (rc != PALSGD_OK) return rc;
     }
+    const uint32_t tiles = tile_count(ctx);
+    const uint32_t lds = lds_cap(waves, 0);
+    float* part = diag_out_dev ? scratch_partials(ctx) : nullptr;
+    const uint32_t n_part = diag_out_dev ? tiles : 0u;
+#define PALSGD_WALK(DIAG, OADAM)                                                                                      \
+    if (deep)                                                                                                         \
+        outer_kernel_walk<DIAG, OADAM, 16><<<tiles, kWave, lds, st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K, a, part, n_part); \
+    else                                                                                                              \
+        outer_kernel_walk<DIAG, OADAM, 8><<<tiles, kWave, lds, st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K, a, part, n_part)
     if (diag_out_dev) {
-        const uint32_t tiles = tile_count(ctx);
-        if (oadam)
-            outer_kernel_walk<true, true><<<tiles, kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K,
-                                                                                  a, scratch_partials(ctx), tiles);
-        else
-            outer_kernel_walk<true, false><<<tiles, kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K,
-                                                                                   a, scratch_partials(ctx), tiles);
+        if (oadam) { PALSGD_WALK(true, true); }
+        else { PALSGD_WALK(true, false); }
         fold_kernel<<<dim3(kFold, 2), kThreads, 0, st>>>(scratch_partials(ctx), tiles, scratch_fold(ctx));
         diag_finish_kernel<<<1, kThreads, 0, st>>>(scratch_fold(ctx), a.inv_k, diag_out_dev);
     } else if (variant == 2) {
@@ -723,12 +729,11 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
         else
             outer_kernel_lds<false><<<blocks, kThreads, lds_cap(groups, 16384), st>>>(b.X, b.XG, b.OM, b.OV, n4, b.row_stride, K, a);
     } else if (oadam) {
-        outer_kernel_walk<false, true><<<tile_count(ctx), kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, b.OV, n,
-                                                                                       b.row_stride, K, a, nullptr, 0);
+        PALSGD_WALK(false, true);
     } else {
-        outer_kernel_walk<false, false><<<tile_count(ctx), kWave, lds_cap(waves, 0), st>>>(b.X, b.XG, b.OM, b.OV, n,
-                                                                                        b.row_stride, K, a, nullptr, 0);
+        PALSGD_WALK(false, false);
     }
+#undef PALSGD_WALK
     palsgd_status rc = check_launch(ctx, who);
     if (rc != PALSGD_OK) return rc;
     ctx->n_outer += 1;
