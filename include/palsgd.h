@@ -306,10 +306,13 @@ palsgd_status palsgd_set_outer_lr(palsgd_ctx *ctx, float outer_lr);
 /* Launch-shape knobs for tuning and tests.  The kernels are throttled to a number of
  * resident wavefronts per compute unit (fewer than the hardware allows streams better);
  * step_waves_per_cu / outer_waves_per_cu override the built-in choice (0 = built-in,
- * else 3..32; 32 = no throttle).  outer_variant: 0 = default choice, 1 = per-lane walk
- * over k, 2 = replicas split over the workgroup's wavefronts with partial sums staged
- * through LDS.  Results do not depend on the wave caps; the two outer variants differ in
- * the order of the K-sum only.  EINVAL on other values. */
+ * else 3..32; 32 = no throttle).  outer_variant: 0 = default choice (1 below K = 32, 3
+ * from there up), 1 = per-lane walk over k in one launch, 2 = replicas split over the
+ * workgroup's wavefronts with partial sums staged through LDS, 3 = the walk without the K
+ * row stores, followed by a second launch that restarts the workers' rows from the new
+ * global model (also used by palsgd_step_sync).  Results do not depend on the wave caps;
+ * variants 1 and 3 are bit-identical, variant 2 differs in the order of the K-sum only.
+ * EINVAL on other values. */
 palsgd_status palsgd_set_tuning(palsgd_ctx *ctx, uint32_t step_waves_per_cu, uint32_t outer_waves_per_cu,
                                 uint32_t outer_variant);
 

@@ -33,13 +33,16 @@ __device__ __forceinline__ f4 outer4(f4 dsum, f4 xg, f4& om, f4& ov, const Outer
 }
 
 // Variant 1: one wavefront per tile; each lane owns four consecutive elements and walks the
-// K rows in ascending order, KU independent loads in flight at a time (8; 16 from K = 32 up, where
-// halving the number of load rounds per wavefront is worth 3 %).
+// K rows in ascending order, eight independent loads in flight at a time.
+// ROWS: the wavefront also stores the new model to the K rows of X (the restart of the workers).  With
+// ROWS = false that is left to restart_rows_kernel in a second launch: from K = 32 up a wavefront that has
+// to issue K stores in a row holds the chip at 5.6 TB/s, while short wavefronts that store a few rows each
+// run the restart alone at the speed of a plain fill.
 // DIAG: also leaves, per wavefront, the partial sums of sum_k |x - x_k|^2 and |Delta|^2
 // (App. A.3) taken from the values already in registers: no extra HBM reads.
 // OADAM: OuterOPT = AdamW (a compile-time switch: as a run-time one it slowed the SGD-family
 // outer step by a quarter).
-template <bool DIAG, bool OADAM, int KU>
+template <bool DIAG, bool OADAM, bool ROWS>
 __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X, float* __restrict__ XG,
                                                            float* __restrict__ OM, float* __restrict__ OV, uint64_t n,
                                                            uint64_t row_stride, uint32_t K, OuterArgs a,
@@ -51,13 +54,13 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
         f4 xg = ld4(XG + e);
         f4 om = ld4(OM + e), ov;
         if (OADAM) ov = ld4(OV + e);
-        for (uint32_t k0 = 0; k0 < K; k0 += KU) {
-            f4 t[KU];
+        for (uint32_t k0 = 0; k0 < K; k0 += 8) {
+            f4 t[8];
 #pragma unroll
-            for (int u = 0; u < KU; ++u)
+            for (int u = 0; u < 8; ++u)
                 if (k0 + u < K) t[u] = ld4(X + (uint64_t)(k0 + u) * row_stride + e);
 #pragma unroll
-            for (int u = 0; u < KU; ++u)
+            for (int u = 0; u < 8; ++u)
                 if (k0 + u < K) {
                     f4 d = xg - t[u];
                     sum += d;
@@ -68,7 +71,8 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
         st4(XG + e, xn);
         st4(OM + e, om);
         if (OADAM) st4(OV + e, ov);
-        for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
+        if (ROWS)
+            for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
     }
     if (DIAG) {
         const f4 delta = sum * a.inv_k;
@@ -82,6 +86,23 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
     }
 }
 
+// Restart of the workers as a launch of its own (Sec. 2.1: every worker continues from the new global model):
+// grid x = tile, y = group of kRestartRows rows, so the chip fills one group of rows after the other and a
+// wavefront lives for one load and kRestartRows stores.  The global model is re-read once per group; it was
+// written by the launch before and is served by the caches while it fits them.
+constexpr int kRestartRows = 8;
+
+__global__ __launch_bounds__(kWave) void restart_rows_kernel(float* __restrict__ X, const float* __restrict__ XG,
+                                                             uint64_t n, uint64_t row_stride, uint32_t K) {
+    const uint64_t e = (uint64_t)blockIdx.x * kTile + threadIdx.x * 4;
+    if (e >= n) return;
+    const f4 v = ld4_cached(XG + e);
+    const uint32_t k0 = blockIdx.y * kRestartRows;
+#pragma unroll
+    for (int u = 0; u < kRestartRows; ++u)
+        if (k0 + u < K) st4(X + (uint64_t)(k0 + u) * row_stride + e, v);
+}
+
 // Last local update of a window fused with the outer step (Alg. 1, step t with (t+1) mod H = 0):
 // a wavefront owns a tile of ALL K rows.  It takes the replicas in ascending order, four at a
 // time (their loads in flight together), applies each replica's branch, stores the InnerOPT
@@ -92,7 +113,7 @@ __global__ __launch_bounds__(kWave) void outer_kernel_walk(float* __restrict__ X
 // roundings are those of step_kernel followed by outer_kernel_walk: results are bit-identical.
 constexpr int kSyncBatch = 4;
 
-template <int INNER, int GDT, bool TAB, bool OADAM>
+template <int INNER, int GDT, bool TAB, bool OADAM, bool ROWS>
 __global__ __launch_bounds__(kWave) void sync_step_kernel(const StepArgs args, const float* __restrict__ wd_tab,
                                                           float* __restrict__ X, float* __restrict__ M,
                                                           float* __restrict__ V, const void* __restrict__ G,
@@ -149,7 +170,8 @@ __global__ __launch_bounds__(kWave) void sync_step_kernel(const StepArgs args, c
     st4(XG + e, xn);
     st4(OM + e, om);
     if (OADAM) st4(OV + e, ov);
-    for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
+    if (ROWS)  // else restart_rows_kernel follows
+        for (uint32_t k = 0; k < K; ++k) st4(X + (uint64_t)k * row_stride + e, xn);
 }
 
 // Variant 2: a workgroup owns a tile of 4 x 256 elements.  Wave w sums the replicas

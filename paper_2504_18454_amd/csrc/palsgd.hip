@@ -332,6 +332,17 @@ palsgd_status alloc_device_state(palsgd_ctx* c) {
     return PALSGD_OK;
 }
 
+// From this many workers on the outer step and the fused synchronisation step leave the K row stores to a
+// second launch (measured: one launch is ahead up to K = 16, the two launches by 12 % at K = 24 and 20 % at K = 64;
+// between 17 and 31 it depends on whether the global model still fits the caches, so the switch sits at 32).
+constexpr uint32_t kSplitOuterFromK = 32;
+
+// X[k] <- XG for all k as short wavefronts, one group of rows after the other, 16 resident per CU.
+void launch_restart_rows(palsgd_ctx* c, hipStream_t st) {
+    dim3 grid(tile_count(c), (c->cfg.K + kRestartRows - 1) / kRestartRows);
+    restart_rows_kernel<<<grid, kWave, lds_cap(16, 0), st>>>(c->buf.X, c->buf.XG, c->P_padded, c->buf.row_stride, c->cfg.K);
+}
+
 template <int INNER, int GDT>
 void launch_step(palsgd_ctx* c, const StepArgs& args, const Slot* dev_slots, uint32_t n_slots, bool any_grad,
                  const float* clip, hipStream_t st) {
@@ -490,14 +501,20 @@ void launch_sync_step(palsgd_ctx* c, const StepArgs& args, const float* clip, co
     const palsgd_buffers& b = c->buf;
     const uint32_t lds = lds_cap(waves, 0);
     const bool oadam = c->cfg.outer_opt == PALSGD_OUTER_ADAMW;
+    const bool split = c->outer_variant == 3 || (c->outer_variant == 0 && K >= kSplitOuterFromK);
 #define PALSGD_SYNC(TAB, OADAM, tab)                                                                               \
-    sync_step_kernel<INNER, GDT, TAB, OADAM><<<tile_count(c), kWave, lds, st>>>(args, tab, b.X, b.M, b.V, b.G, b.XG, b.OM, \
-                                                                               b.OV, clip, c->P_padded, b.row_stride, K, h, a)
-    if (c->wd_uniform && !oadam) PALSGD_SYNC(false, false, nullptr);
-    else if (c->wd_uniform) PALSGD_SYNC(false, true, nullptr);
-    else if (!oadam) PALSGD_SYNC(true, false, c->d_wd_tab);
-    else PALSGD_SYNC(true, true, c->d_wd_tab);
+    if (split)                                                                                                     \
+        sync_step_kernel<INNER, GDT, TAB, OADAM, false><<<tile_count(c), kWave, lds, st>>>(                        \
+            args, tab, b.X, b.M, b.V, b.G, b.XG, b.OM, b.OV, clip, c->P_padded, b.row_stride, K, h, a);            \
+    else                                                                                                           \
+        sync_step_kernel<INNER, GDT, TAB, OADAM, true><<<tile_count(c), kWave, lds, st>>>(                         \
+            args, tab, b.X, b.M, b.V, b.G, b.XG, b.OM, b.OV, clip, c->P_padded, b.row_stride, K, h, a)
+    if (c->wd_uniform && !oadam) { PALSGD_SYNC(false, false, nullptr); }
+    else if (c->wd_uniform) { PALSGD_SYNC(false, true, nullptr); }
+    else if (!oadam) { PALSGD_SYNC(true, false, c->d_wd_tab); }
+    else { PALSGD_SYNC(true, true, c->d_wd_tab); }
 #undef PALSGD_SYNC
+    if (split) launch_restart_rows(c, st);
 }
 
 }  // namespace
@@ -694,10 +711,10 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
     const uint64_t n = ctx->P_padded;
     hipStream_t st = (hipStream_t)stream;
     const uint32_t variant = ctx->outer_variant ? ctx->outer_variant : 1u;
-    // Rows go 8 at a time and 4 resident wavefronts per CU are best from K = 16 up; from K = 32 up 16 at a time
-    // and 3 wavefronts (sweeps of both, K = 4 .. 64).
-    const bool deep = K >= 32;
-    const uint32_t waves = ctx->outer_waves ? ctx->outer_waves : (deep ? 3u : auto_waves((8u * K + 16u) * kTile, 4));
+    // One launch up to K = 31 (rows go 8 at a time; 4 resident wavefronts per CU are best from K = 16 up).  From
+    // K = 32 up (or variant 3) two: the reduction with OuterOPT, 6 wavefronts per CU, then the restart of the rows.
+    const bool split = ctx->outer_variant == 3 || (ctx->outer_variant == 0 && K >= kSplitOuterFromK);
+    const uint32_t waves = ctx->outer_waves ? ctx->outer_waves : (split ? 6u : auto_waves((8u * K + 16u) * kTile, 4));
     const palsgd_buffers& b = ctx->buf;
     const bool oadam = ctx->cfg.outer_opt == PALSGD_OUTER_ADAMW;
     {
@@ -711,10 +728,10 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
     float* part = diag_out_dev ? scratch_partials(ctx) : nullptr;
     const uint32_t n_part = diag_out_dev ? tiles : 0u;
 #define PALSGD_WALK(DIAG, OADAM)                                                                                      \
-    if (deep)                                                                                                         \
-        outer_kernel_walk<DIAG, OADAM, 16><<<tiles, kWave, lds, st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K, a, part, n_part); \
+    if (split)                                                                                                        \
+        outer_kernel_walk<DIAG, OADAM, false><<<tiles, kWave, lds, st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K, a, part, n_part); \
     else                                                                                                              \
-        outer_kernel_walk<DIAG, OADAM, 8><<<tiles, kWave, lds, st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K, a, part, n_part)
+        outer_kernel_walk<DIAG, OADAM, true><<<tiles, kWave, lds, st>>>(b.X, b.XG, b.OM, b.OV, n, b.row_stride, K, a, part, n_part)
     if (diag_out_dev) {
         if (oadam) { PALSGD_WALK(true, true); }
         else { PALSGD_WALK(true, false); }
@@ -734,6 +751,7 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
         PALSGD_WALK(false, false);
     }
 #undef PALSGD_WALK
+    if (split) launch_restart_rows(ctx, st);
     palsgd_status rc = check_launch(ctx, who);
     if (rc != PALSGD_OK) return rc;
     ctx->n_outer += 1;
@@ -1111,8 +1129,8 @@ palsgd_status palsgd_set_tuning(palsgd_ctx* ctx, uint32_t step_waves_per_cu, uin
         return PALSGD_EINVAL;
     }
     auto bad = [](uint32_t w) { return w != 0 && (w < 3 || w > 32); };
-    if (bad(step_waves_per_cu) || bad(outer_waves_per_cu) || outer_variant > 2) {
-        set_error(ctx->error, "palsgd_set_tuning: waves per CU must be 0 or 3..32, outer_variant 0..2");
+    if (bad(step_waves_per_cu) || bad(outer_waves_per_cu) || outer_variant > 3) {
+        set_error(ctx->error, "palsgd_set_tuning: waves per CU must be 0 or 3..32, outer_variant 0..3");
         return PALSGD_EINVAL;
     }
     ctx->step_waves = step_waves_per_cu;

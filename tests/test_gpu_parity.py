@@ -75,7 +75,8 @@ def test_inner_nesterov_momentum(grad_dtype, K, wd_mult):
     r.close(); h.close()
 
 
-@pytest.mark.parametrize("variant,step_waves,outer_waves", [(1, 3, 3), (2, 32, 4), (1, 0, 32), (2, 11, 0), (2, 5, 8)])
+@pytest.mark.parametrize("variant,step_waves,outer_waves", [(1, 3, 3), (2, 32, 4), (1, 0, 32), (2, 11, 0), (2, 5, 8), (3, 0, 0),
+                                                            (3, 7, 16)])
 def test_tuning_shapes_agree_with_oracle(variant, step_waves, outer_waves):
     r = _run(K=6, numels=[100000, 64, 777, 40000], inner="adamw", grad_dtype="bf16", p=0.2, H=3, seed=15,
              wd_mult=[1, 0, 0, 1], row_extra=1)
@@ -467,6 +468,27 @@ def test_fused_sync_step_equals_step_plus_outer(inner, grad_dtype, K):
     a.compare(); b.compare()
     for ta, tb in ((a.X, b.X), (a.M, b.M), (a.XG, b.XG), (a.OM, b.OM)) + (((a.V, b.V),) if a.V is not None else ()):
         assert torch.equal(ta, tb)
+    a.close(); b.close()
+
+
+@pytest.mark.parametrize("K,inner", [(5, "adamw"), (40, "sgdm")])
+def test_outer_step_in_one_launch_and_in_two_is_the_same(K, inner):
+    """Variant 3 (reduction + OuterOPT, then the restart of the K rows as a launch of its own; the default from
+    K = 32 up) against variant 1 (everything in one launch): same sums in the same order, so the same bits, for the
+    outer step, the outer step with diagnostics and the fused synchronisation step; a ragged last row group
+    (K = 5 and 40 are not multiples of the eight rows a restart wavefront stores)."""
+    kw = dict(K=K, numels=RAGGED, inner=inner, p=0.3, H=2, seed=200 + K, sigma=0.05, row_extra=1)
+    a, b = _run(**kw), _run(**kw)
+    a.lib.palsgd_set_tuning(0, 0, 1)
+    b.lib.palsgd_set_tuning(0, 0, 3)
+    for r in (a, b):
+        r.iterate(4)
+        r.iterate(2, diag_outer=True)
+        r.iterate(2, fused_sync=True)
+        r.compare()
+    for ta, tb in ((a.X, b.X), (a.M, b.M), (a.XG, b.XG), (a.OM, b.OM)):
+        assert torch.equal(ta, tb)
+    assert a.last_diag == b.last_diag
     a.close(); b.close()
 
 

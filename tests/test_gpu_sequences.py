@@ -66,7 +66,7 @@ def test_random_call_sequence(seed):
                 r.iterate(1, mask_fn=lambda t: mask, fused=bool(rng.integers(2)))
             elif op == "tuning":                                # launch shapes: results may differ in the K-sum order only
                 r.lib.palsgd_set_tuning(int(rng.choice([0, 3, 8, 32])), int(rng.choice([0, 3, 4, 32])),
-                                        int(rng.choice([0, 1, 2])))
+                                        int(rng.choice([0, 1, 2, 3])))
             elif op in ("ddp", "ddp_shared", "clip_ddp"):
                 if not _identical_step_counts(r, shared):               # the DDP step needs identical workers: refused, nothing changes
                     with pytest.raises(PalsgdError) as e:

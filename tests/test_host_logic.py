@@ -129,7 +129,7 @@ def test_state_roundtrip_and_step_argument_errors():
     assert lib().palsgd_inner_step(ctx, 0, 1e-3, gs, (C.c_uint8 * 3)(1, 0, 1), None) == binding.PALSGD_EINVAL
     assert lib().palsgd_set_tuning(ctx, 2, 0, 0) == binding.PALSGD_EINVAL
     assert lib().palsgd_set_tuning(ctx, 0, 33, 0) == binding.PALSGD_EINVAL
-    assert lib().palsgd_set_tuning(ctx, 0, 0, 3) == binding.PALSGD_EINVAL
+    assert lib().palsgd_set_tuning(ctx, 0, 0, 4) == binding.PALSGD_EINVAL
     assert lib().palsgd_set_tuning(ctx, 12, 4, 2) == 0
     assert lib().palsgd_get_state(ctx, got, C.byref(n)) == 0 and list(got) == [5, 6, 7]    # state untouched
     # nothing to do is not an error and launches nothing: every worker mixes, inner_step skips all
