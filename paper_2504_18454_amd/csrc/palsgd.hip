@@ -814,8 +814,10 @@ static palsgd_status ddp_impl(palsgd_ctx* ctx, const char* who, float alpha_t, c
     }
     const uint64_t n = ctx->P_padded;
     const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
-    // rows of X this launch stores: all K, or none when the model stays shared (it is then XG alone)
-    const uint32_t x_rows = share_model ? 0u : K;
+    // rows of X this launch stores: all K, or none when the model stays shared (it is then XG alone) and when
+    // the rows are many enough for a restart launch of their own to be faster (as in the outer step)
+    const bool rows_apart = !share_model && K >= kSplitOuterFromK;
+    const uint32_t x_rows = share_model || rows_apart ? 0u : K;
     const uint32_t per_elem = (adamw ? 24u : 16u) + 4u * x_rows + K * (bf16 ? 2u : 4u);
     const uint32_t lds = lds_cap(ctx->outer_waves ? ctx->outer_waves : auto_waves(per_elem * kTile, 4), 0);
     Hyper h = hyper_of(ctx);
@@ -836,6 +838,7 @@ static palsgd_status ddp_impl(palsgd_ctx* ctx, const char* who, float alpha_t, c
     else if (bf16) { PALSGD_DDP(PALSGD_INNER_SGDM, PALSGD_GRAD_BF16) }
     else { PALSGD_DDP(PALSGD_INNER_SGDM, PALSGD_GRAD_F32) }
 #undef PALSGD_DDP
+    if (rows_apart) launch_restart_rows(ctx, st);
     palsgd_status rc = check_launch(ctx, who);
     if (rc != PALSGD_OK) return rc;
     for (uint32_t k = 0; k < K; ++k) ctx->tau[k] += 1;
