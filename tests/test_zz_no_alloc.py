@@ -36,7 +36,11 @@ def _case(K, numels, grad_dtype, seed, max_norm):
             G[k].copy_(torch.empty(row, dtype=f, device=dev).normal_(0.0, 0.5 + 0.25 * k, generator=gen) * real)
         lib = Palsgd(cfg, X, M, V, G, XG, OM, row, x0=x0)
         norms = torch.full((K,), -1.0, dtype=f, device=dev)
+        torch.cuda.synchronize()
+        free_before = torch.cuda.mem_get_info()[0]
         getattr(lib, entry)(max_norm, norms)
+        torch.cuda.synchronize()
+        assert torch.cuda.mem_get_info()[0] == free_before, "the call changed the amount of free device memory"
         lib.palsgd_step(0, 1e-3, 16.0, [1.0 + 0.5 * k for k in range(K)])      # consumes the scales
         torch.cuda.synchronize()
         outs.append(dict(norms=norms.cpu().numpy(), X=X.clone(), M=M.clone(), V=V.clone(), G=G, row=row, offs=offs,
