@@ -148,6 +148,34 @@ def test_minimal_row_and_p_zero():
     r.close()
 
 
+@pytest.mark.parametrize("case", ["H1_averaging", "H1_fused", "p_near_one", "single_worker", "K64_H1"])
+def test_degenerate_cases(case):
+    """The corners of Alg. 1: a synchronisation at every step (H = 1; with outer lr 1 and no momentum the workers
+    are averaged each step, Sec. 3.1), almost every step a mixing step (p = 0.9, so InnerOPT runs at 10 alpha),
+    one worker (the outer gradient is that worker's own movement), the largest worker count at H = 1."""
+    if case in ("H1_averaging", "H1_fused"):
+        r = _run(K=4, numels=RAGGED, inner="sgdm", p=0.0, H=1, seed=301, outer_lr=1.0, outer_momentum=0.0,
+                 outer_nesterov=False, sigma=0.05)
+        r.iterate(6, fused_sync=case == "H1_fused")
+        for k in range(4):
+            assert torch.equal(r.X[k], r.XG)
+        assert r.lib.palsgd_get_state() == ([6] * 4, 6)
+    elif case == "p_near_one":
+        r = _run(K=8, numels=RAGGED, grad_dtype="bf16", p=0.9, H=4, eta=2.0, seed=302, sigma=0.05)
+        r.iterate(12)
+        tau, _ = r.lib.palsgd_get_state()
+        assert sum(tau) < 8 * 12 // 3                    # most of the 96 worker-steps mixed
+    elif case == "single_worker":
+        r = _run(K=1, numels=RAGGED, p=0.3, H=2, seed=303, outer_lr=1.0, outer_momentum=0.0, outer_nesterov=False, row_extra=1)
+        r.iterate(7, fused_sync=True)
+    else:
+        r = _run(K=64, numels=[3000, 64, 1], inner="sgdm", grad_dtype="bf16", p=0.25, H=1, seed=304, sigma=0.05)
+        r.iterate(5)
+        r.iterate(3, fused_sync=True)
+    r.compare()
+    r.close()
+
+
 def test_resume_from_state():
     a = _run(K=3, numels=[5000, 70], p=0.3, H=4, seed=18)
     a.iterate(6)
