@@ -10,7 +10,8 @@ in HBM when the timed region starts.  Prints ONE JSON line:
   roofline    the fused local-update kernel against the HBM peak: algorithmic bytes per
               launch (26 B per replica-element on the AdamW/bf16 gradient branch, 28 fp32,
               20 SGD-momentum, 12 on the mixing branch) over its mean launch duration,
-              measured with HIP events on the launch stream inside the timed region
+              measured with HIP events on the launch stream inside the timed region (one event per launch
+              boundary: a launch's duration runs to the start of the next)
   cpu_baseline the CPU oracle timed on a bounded slice of the same workload
 
     python bench.py [--gpus 1] [--steps 256] [--warmup 64] [--workload gptneo125m_k8]
@@ -38,7 +39,7 @@ HBM_PEAK_GBPS = 8000.0
 TRAFFIC = {
     "workload": "gptneo125m_k8",
     "kernel_source_sha256": "2b4b472afa213a9d7fc1d8fd969690649f8cde613eeda7b322a7d303d24f09fa",
-    "bytes_per_launch": 25224125198.9,            # mean over the 16 launches t = 0..15 of the counter runs
+    "bytes_per_launch": 25224111946.2,            # mean over the 16 launches t = 0..15 of the counter runs
     "algorithmic_bytes_same_launches": 25224565440.0,
 }
 
@@ -127,22 +128,24 @@ def run_gpu(w, steps, warmup, reps, step_waves, outer_waves, outer_variant, extr
         ctx.palsgd_set_tuning(step_waves, outer_waves, outer_variant)
     torch.cuda.synchronize()
 
-    def one(t, ev=None):
-        if ev is not None:
-            ev[0].record(stream)
+    def one(t, marks=None):
+        """Step t of Alg. 1.  marks: list that receives one HIP event per launch boundary of this step, recorded on the
+        launch stream: before the local update, and on a synchronisation step between it and the outer step.  The
+        next step's first event (or the window's closing one) ends the last launch, so a launch costs one event
+        record, not two (on the 8.4M-parameter workload three records per step cost 5 % of the step)."""
+        def mark():
+            if marks is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record(stream)
+                marks.append(e)
+        mark()
         if fused_sync and (t + 1) % w.H == 0:          # the synchronisation step as one launch
             ctx.palsgd_step_sync(t, w.alpha, w.eta, None, None, stream)
-            if ev is not None:
-                ev[1].record(stream)
-                ev[2].record(stream)
             return True
         ctx.palsgd_step(t, w.alpha, w.eta, None, None, stream)
-        if ev is not None:
-            ev[1].record(stream)
         if (t + 1) % w.H == 0:
+            mark()
             ctx.palsgd_outer_step(t, stream)
-            if ev is not None:
-                ev[2].record(stream)
             return True
         return False
 
@@ -154,34 +157,43 @@ def run_gpu(w, steps, warmup, reps, step_waves, outer_waves, outer_variant, extr
     P = w.P
     gb, mb = grad_bytes_per_elem(w.inner, w.grad_dtype), 12
     outer_bytes = float(P) * (8 * K + 16)
-    windows, all_ms, all_bytes, outer_ms, fused_ms = [], [], [], [], []
+    windows, outer_ms, fused_ms = [], [], []
     t_next = warmup
     for _ in range(reps):
-        events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        marks = []
         masks = [ctx.palsgd_draw(t) for t in range(t_next, t_next + steps)]
         synced = []
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            synced.append(one(t_next + i, events[i]))
+            synced.append(one(t_next + i, marks))
+        closing = torch.cuda.Event(enable_timing=True)
+        closing.record(stream)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         t_next += steps
-        ms = [events[i][0].elapsed_time(events[i][1]) for i in range(steps)]
+        marks.append(closing)
         by = [float(P) * ((K - int(m.sum())) * gb + int(m.sum()) * mb) for m in masks]
         n_sync = sum(synced)
+        all_ms, all_bytes = [], []                       # this window's launches of step_kernel
+        j = 0                                            # index of the event that opens step i
         for i in range(steps):
+            ms = marks[j].elapsed_time(marks[j + 1])     # the local update (or the fused synchronisation step)
             if fused_sync and synced[i]:
-                fused_ms.append(ms[i])
+                fused_ms.append(ms)
             else:
-                all_ms.append(ms[i])
+                all_ms.append(ms)
                 all_bytes.append(by[i])
+            j += 1
             if synced[i] and not fused_sync:
-                outer_ms.append(events[i][1].elapsed_time(events[i][2]))
+                outer_ms.append(marks[j].elapsed_time(marks[j + 1]))
+                j += 1
+        assert j == len(marks) - 1
         windows.append(dict(elapsed=elapsed, n_outer=n_sync, bytes=sum(by) + outer_bytes * n_sync,
-                            mix=float(np.mean([m.mean() for m in masks]))))
+                            mix=float(np.mean([m.mean() for m in masks])), step_ms=all_ms, step_bytes=all_bytes))
     order = sorted(range(reps), key=lambda r: windows[r]["elapsed"])
     med = windows[order[len(order) // 2]]
+    all_ms, all_bytes = med["step_ms"], med["step_bytes"]   # the roofline figure is that of the window `value` is quoted on
 
     # every kernel of the path alone, right after the windows, with events on the launch stream around each launch:
     # the outer step (after an untimed local update, as in Alg. 1), the fused synchronisation step, and each branch
@@ -217,7 +229,7 @@ def run_gpu(w, steps, warmup, reps, step_waves, outer_waves, outer_variant, extr
     outer_med = float(np.median(outer_ms + alone_outer))
     bytes_mean = float(np.mean(all_bytes))
     res = dict(
-        elapsed=med["elapsed"], updates=float(K) * P * steps, row=row, reps=reps,
+        elapsed=med["elapsed"], updates=float(K) * P * steps, row=row, reps=reps, median_window=order[len(order) // 2],
         window_ms_per_step=[windows[r]["elapsed"] / steps * 1e3 for r in order],
         window_outer_steps=[windows[r]["n_outer"] for r in order],
         n_outer=med["n_outer"], mix_fraction=med["mix"], blended_gbps=med["bytes"] / med["elapsed"] / 1e9,
@@ -388,7 +400,8 @@ def main():
                    "mix_fraction_timed": round(r["mix_fraction"], 4),
                    "weight_decay": "uniform" if not a.no_decay_1d else "per tensor: 0 on 1-D tensors"},
         # value and ms_per_step are the MEDIAN of `reps` timed windows of `steps` steps each (sorted list beside it)
-        "reps": r["reps"], "ms_per_step_of_each_window_sorted": r["window_ms_per_step"],
+        # (median_window: its index in time order, from 0; the roofline figures are those of its launches)
+        "reps": r["reps"], "median_window": r["median_window"], "ms_per_step_of_each_window_sorted": r["window_ms_per_step"],
         "outer_steps_in_each_window_sorted": r["window_outer_steps"],
         "hbm_GBps_whole_step": r["blended_gbps"], "hbm_frac_whole_step": r["blended_gbps"] / HBM_PEAK_GBPS,
         # one step of Alg. 1 with 1/H of a synchronisation step's outer launch, from kernel event times
