@@ -71,6 +71,8 @@ typedef enum { PALSGD_OUTER_SGD = 0, PALSGD_OUTER_ADAMW = 1 } palsgd_outer_opt;
 typedef struct {
     uint32_t K;                   /* workers, 1..PALSGD_MAX_K                               */
     uint32_t n_tensors;           /* >= 1                                                   */
+    uint64_t P;                   /* logical parameter count: 0 = not stated, else it must
+                                     equal the sum of tensor_numel (checked: EINVAL)         */
     const uint64_t *tensor_numel; /* host array [n_tensors], each >= 1; copied at init      */
     const float *tensor_wd_mult;  /* host array [n_tensors] or NULL (= 1): per-tensor
                                      multiplier on weight_decay                             */
@@ -105,7 +107,8 @@ typedef struct {
 /* Flat layout of a row: tensor_offset[j] (host array [n_tensors], may be NULL) is the
  * start element of tensor j, each start rounded up to a multiple of 64; *P_padded is
  * the padded row length, rounded up to a multiple of 256.  Only K-independent fields of the config are read
- * (n_tensors, tensor_numel).  EINVAL on NULL pointers, n_tensors == 0 or a zero numel. */
+ * (n_tensors, tensor_numel, P).  EINVAL on NULL pointers, n_tensors == 0, a zero numel, or
+ * a non-zero P that is not the sum of tensor_numel. */
 palsgd_status palsgd_layout(const palsgd_config *cfg, uint64_t *P_padded, uint64_t *tensor_offset);
 
 /* Alg. 1, initialisation x_k^(0) <- x^(0): creates a context over the caller's buffers.  If x0_dev

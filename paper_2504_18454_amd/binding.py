@@ -38,7 +38,7 @@ class PalsgdError(RuntimeError):
 
 
 class Config(C.Structure):
-    _fields_ = [("K", C.c_uint32), ("n_tensors", C.c_uint32),
+    _fields_ = [("K", C.c_uint32), ("n_tensors", C.c_uint32), ("P", C.c_uint64),
                 ("tensor_numel", C.POINTER(C.c_uint64)), ("tensor_wd_mult", C.POINTER(C.c_float)),
                 ("inner", C.c_int32), ("grad_dtype", C.c_int32),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
@@ -133,6 +133,7 @@ def make_config(K: int, tensor_numel: Sequence[int], *, inner: str = "adamw", gr
     numel = (C.c_uint64 * max(n, 1))(*[int(v) for v in tensor_numel])
     cfg._keep = [numel]                              # keep the host arrays alive with the struct
     cfg.K, cfg.n_tensors = int(K), n
+    cfg.P = sum(int(v) for v in tensor_numel)        # stated, so that the library checks it against the tensor list
     cfg.tensor_numel = C.cast(numel, C.POINTER(C.c_uint64))
     if wd_mult is not None:
         wm = (C.c_float * max(n, 1))(*[float(v) for v in wd_mult])

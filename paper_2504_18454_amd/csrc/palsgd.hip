@@ -147,13 +147,13 @@ namespace {
 // One lane per four elements and fewer than 2^32 work-items per launch dimension: rows below 2^34 elements.
 constexpr uint64_t kMaxRow = 1ull << 33;
 
-palsgd_status layout_impl(uint32_t n_tensors, const uint64_t* numel, uint64_t* P_padded, uint64_t* offs,
-                          char* err) {
+palsgd_status layout_impl(uint32_t n_tensors, const uint64_t* numel, uint64_t P_stated, uint64_t* P_padded,
+                          uint64_t* offs, char* err) {
     if (!numel || !P_padded || n_tensors == 0) {
         set_error(err, "palsgd_layout: NULL argument or n_tensors == 0");
         return PALSGD_EINVAL;
     }
-    uint64_t cur = 0;
+    uint64_t cur = 0, total = 0;
     for (uint32_t j = 0; j < n_tensors; ++j) {
         if (numel[j] == 0) {
             set_error(err, "palsgd_layout: tensor %u has zero elements", j);
@@ -161,6 +161,12 @@ palsgd_status layout_impl(uint32_t n_tensors, const uint64_t* numel, uint64_t* P
         }
         if (offs) offs[j] = cur;
         cur = (cur + numel[j] + 63u) / 64u * 64u;
+        total += numel[j];
+    }
+    if (P_stated != 0 && P_stated != total) {
+        set_error(err, "palsgd_layout: P = %llu but the tensors hold %llu elements", (unsigned long long)P_stated,
+                  (unsigned long long)total);
+        return PALSGD_EINVAL;
     }
     // rows end on a tile boundary: with row_stride = P_padded every wavefront's 1 KiB access is 1 KiB-aligned
     // in every row (rows shifted against each other by 256 B measured 3 % slower)
@@ -526,7 +532,7 @@ palsgd_status palsgd_layout(const palsgd_config* cfg, uint64_t* P_padded, uint64
         set_error(g_error, "palsgd_layout: NULL config");
         return PALSGD_EINVAL;
     }
-    return layout_impl(cfg->n_tensors, cfg->tensor_numel, P_padded, tensor_offset, g_error);
+    return layout_impl(cfg->n_tensors, cfg->tensor_numel, cfg->P, P_padded, tensor_offset, g_error);
 }
 
 palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, const float* x0_dev, void* stream,
@@ -538,7 +544,7 @@ palsgd_status palsgd_init(const palsgd_config* cfg, const palsgd_buffers* buf, c
     }
     uint64_t P_padded = 0;
     std::vector<uint64_t> offs(cfg->n_tensors ? cfg->n_tensors : 1);
-    palsgd_status rc = layout_impl(cfg->n_tensors, cfg->tensor_numel, &P_padded, offs.data(), g_error);
+    palsgd_status rc = layout_impl(cfg->n_tensors, cfg->tensor_numel, cfg->P, &P_padded, offs.data(), g_error);
     if (rc != PALSGD_OK) return rc;
 #define PALSGD_REQUIRE(cond, msg)                          \
     if (!(cond)) {                                         \

@@ -41,7 +41,8 @@ def test_layout_pads_tensors_to_64_rows_to_256_and_matches_generator_layout():
 
 
 def _init(cfg, **over):
-    b = dict(X=FAKE, M=FAKE, V=FAKE, G=FAKE, XG=FAKE, OM=FAKE, row_stride=palsgd_layout(cfg)[0])
+    b = dict(X=FAKE, M=FAKE, V=FAKE, G=FAKE, XG=FAKE, OM=FAKE)
+    b["row_stride"] = over["row_stride"] if "row_stride" in over else palsgd_layout(cfg)[0]
     b.update(over)
     out = C.c_void_p()
     st = lib().palsgd_init(C.byref(cfg), C.byref(Buffers(**b)), None, None, C.byref(out))
@@ -74,6 +75,17 @@ def test_init_rejects_bad_arguments_without_touching_the_device():
     cfg = make_config(2, [2 ** 33 + 1])
     st, out = _init(cfg)
     assert st == binding.PALSGD_EINVAL and not out.value and b"2^33" in lib().palsgd_last_error(None)
+    # a stated parameter count that is not the sum of the tensor sizes
+    cfg = make_config(2, [100, 7])
+    cfg.P = 108
+    st, out = _init(cfg, row_stride=256)
+    assert st == binding.PALSGD_EINVAL and not out.value and b"107" in lib().palsgd_last_error(None)
+    with pytest.raises(binding.PalsgdError, match="107"):
+        palsgd_layout(cfg)
+    cfg.P = 0                                               # not stated: accepted
+    st, out = _init(cfg)
+    assert st == binding.PALSGD_OK
+    lib().palsgd_destroy(out)
     # empty model and zero-sized tensor
     for numels in ([], [5, 0]):
         cfg = make_config(2, numels)
