@@ -365,7 +365,7 @@ def main():
                     help="also time the DDP warm-up step, gradient-norm clipping and diagnostics kernels")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (K replicas share it); --gpus must be 1. "
+        print("bench.py: this library runs on ONE GPU (K replicas share it); --gpus must be 1. "
               "No multi-GPU figure exists for it.", file=sys.stderr)
         sys.exit(2)
     if a.reps < 1 or a.steps < 1:
