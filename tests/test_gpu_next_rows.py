@@ -176,9 +176,9 @@ def test_ddp_rejects_diverged_workers():
 
 # Two input scales.  "small": targets c ~ 0.25 N(0,1), noise 0.1, so |g_hat| stays below 2 and the tolerance holds
 # with its fixed 1e-7 floor on every array.  "unit": the benchmark configurations' own scale, c ~ N(0,1), noise
-# 0.5, caller-side multipliers up to 2, so unclipped |g_hat| reaches 9; there the first moment's floor is stated
-# in units of the largest |g_hat| its position has seen (Run(moment_floor_by_gradient=True)), every other array
-# keeps the fixed floor.
+# 0.5, caller-side multipliers up to 2, so unclipped |g_hat| reaches 9.  There every array of an AdamW run still
+# keeps the fixed floor; the SGD-momentum buffer, a sum of about ten gradients, has its floor stated in units of
+# the largest |g_hat| and |buf| of its row (Run(moment_floor_by_gradient=True)).
 SCALES = {"small": dict(sigma=0.1, c_scale=0.25), "unit": dict(sigma=0.5, c_scale=1.0, moment_floor_by_gradient=True)}
 
 
