@@ -28,6 +28,10 @@
 //   outer_kernel_* Alg. 1 outer step: K-way mean of the differences x - x_k, OuterOPT with
 //                  (Nesterov) momentum, restart of the K workers; optionally the
 //                  consensus-distance diagnostics from the values already in registers.
+//   restart_rows_kernel
+//                  the restart of the K workers as a launch of its own, used from K = 32 up:
+//                  short store-only wavefronts fill the rows faster than a reducing
+//                  wavefront that has K stores to issue.
 //   init_kernel    x_k^(0) <- x^(0), cleared optimizer state.
 //   ddp_kernel     DDP step of the warm-up phase: K-way gradient mean + one InnerOPT step.
 //   plan_kernel    device-resident schedule (draws, step counts, bias corrections) for
@@ -35,6 +39,9 @@
 //   sumsq_kernel, diag_kernel, fold_kernel, *_finish_kernel
 //                  scalar reductions (gradient norms for clipping, consensus distance):
 //                  lane-local sums, a shuffle tree per wavefront, fixed-order folds in double.
+//
+// All device memory of the library (weight-decay table, reduction scratch, device schedule) is
+// allocated by palsgd_init; no other entry point allocates, so each may be captured in a HIP graph.
 //
 // No matrix cores: nothing here is a contraction.  No data goes through LDS in the step
 // kernel: there is no reuse to stage.  Each XCD's private L2 is irrelevant to pure
