@@ -246,3 +246,16 @@ def test_plain_c_program_is_built_and_fails_cleanly_without_a_gpu():
     out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert out.returncode in (0, 2), (out.returncode, out.stderr)
     assert ("HIP error" in out.stderr) if out.returncode == 2 else ("PASS" in out.stdout)
+
+
+def test_input_generators_import_nothing_of_the_device_path():
+    """The seeded input generators serve the device path's tests and the CPU checker's alike; importing them
+    alone must not bring in the binding (or the checker)."""
+    import subprocess
+    import sys
+    code = ("import sys; import paper_2504_18454_amd.workloads as w; "
+            "assert 'paper_2504_18454_amd.binding' not in sys.modules and 'oracle' not in sys.modules and 'ctypes' not in "
+            "[m for m in sys.modules if m == 'paper_2504_18454_amd.binding']; print(len(w.WORKLOADS))")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=root)
+    assert out.returncode == 0 and out.stdout.strip() == "6", out.stderr
