@@ -153,8 +153,8 @@ palsgd_status palsgd_step(palsgd_ctx *ctx, uint64_t t, float alpha_t, float eta_
                           const float *grad_scale, const uint8_t *mask_override, void *stream);
 
 /* Step t of Alg. 1 when (t+1) mod H == 0, whole: palsgd_step followed by
- * palsgd_outer_step fused into ONE launch (from K = 32 up followed by the launch that
- * restarts the workers' rows, as in palsgd_outer_step), with identical results.  The local update's new x_k
+ * palsgd_outer_step fused into ONE launch (followed by the launch that restarts the
+ * workers' rows where palsgd_outer_step uses one), with identical results.  The local update's new x_k
  * stay in registers and go straight into the outer gradient, which saves one write and
  * one read of the K rows of X (8K of 34K+16 bytes per element with AdamW).  Arguments as
  * palsgd_step. */
@@ -164,10 +164,10 @@ palsgd_status palsgd_step_sync(palsgd_ctx *ctx, uint64_t t, float alpha_t, float
 /* Outer step (Alg. 1, the two lines of the synchronisation branch; Sec. 4.2):
  * Delta = XG - (1/K) sum_k X[k];  OM <- mu OM + Delta;
  * XG <- XG - outer_lr (Delta + mu OM) (Nesterov) or XG - outer_lr OM;  X[k] <- XG for
- * all k (Sec. 2.1: workers restart from the global model).  One launch below K = 32; from
- * there up the restart of the K rows is a second launch on the same stream (short
- * wavefronts that store eight rows each fill them 20 % faster than the reducing wavefronts
- * can).  With outer_opt = AdamW:
+ * all k (Sec. 2.1: workers restart from the global model).  One launch; with K >= 24 and
+ * rows of at most 192 MiB (the global model then stays in the memory-side cache) the restart
+ * of the K rows is a second launch on the same stream: short wavefronts that store eight
+ * rows each fill them 5-20 % faster than the reducing wavefronts can.  With outer_opt = AdamW:
  * OM <- b1 OM + (1-b1) Delta, OV <- b2 OV + (1-b2) Delta^2,
  * XG <- XG - outer_lr ((OM/(1-b1^n)) / (sqrt(OV/(1-b2^n)) + eps) + wd XG), n = number of
  * this outer step (from 1; part of palsgd_get_state / palsgd_set_state).  The bias
@@ -187,7 +187,7 @@ palsgd_status palsgd_outer_step_diag(palsgd_ctx *ctx, uint64_t t, float *diag_ou
  * gradient at every step before the optimizer update; Sec. 4.3, Sec. 5.1):
  * gbar = (1/K) sum_k grad_scale[k] G[k];  x <- InnerOPT(x, gbar, alpha_t) (no 1/(1-p)
  * rescale: there is no mixing branch);  the result is stored to XG and to every row of X
- * (from K = 32 up by the same second launch as in palsgd_outer_step), and every worker's
+ * (by a second launch under the same condition as in palsgd_outer_step), and every worker's
  * step count advances.  The InnerOPT state of the identical workers
  * is kept once, in worker 0's rows of M, V; rows 1..K-1 are stale during the warm-up and
  * are filled from row 0 by the first palsgd_inner_step / palsgd_pseudo_sync / palsgd_step /
@@ -314,8 +314,8 @@ palsgd_status palsgd_set_outer_lr(palsgd_ctx *ctx, float outer_lr);
 /* Launch-shape knobs for tuning and tests.  The kernels are throttled to a number of
  * resident wavefronts per compute unit (fewer than the hardware allows streams better);
  * step_waves_per_cu / outer_waves_per_cu override the built-in choice (0 = built-in,
- * else 3..32; 32 = no throttle).  outer_variant: 0 = default choice (1 below K = 32, 3
- * from there up), 1 = per-lane walk over k in one launch, 2 = replicas split over the
+ * else 3..32; 32 = no throttle).  outer_variant: 0 = default choice (3 for K >= 24 with rows
+ * of at most 192 MiB, else 1), 1 = per-lane walk over k in one launch, 2 = replicas split over the
  * workgroup's wavefronts with partial sums staged through LDS, 3 = the walk without the K
  * row stores, followed by a second launch that restarts the workers' rows from the new
  * global model (also used by palsgd_step_sync).  Results do not depend on the wave caps;

@@ -35,9 +35,9 @@ __device__ __forceinline__ f4 outer4(f4 dsum, f4 xg, f4& om, f4& ov, const Outer
 // Variant 1: one wavefront per tile; each lane owns four consecutive elements and walks the
 // K rows in ascending order, eight independent loads in flight at a time.
 // ROWS: the wavefront also stores the new model to the K rows of X (the restart of the workers).  With
-// ROWS = false that is left to restart_rows_kernel in a second launch: from K = 32 up a wavefront that has
+// ROWS = false that is left to restart_rows_kernel in a second launch: with many workers a wavefront that has
 // to issue K stores in a row holds the chip at 5.6 TB/s, while short wavefronts that store a few rows each
-// run the restart alone at the speed of a plain fill.
+// run the restart alone at the speed of a plain fill (as long as the model they re-read comes from the caches).
 // DIAG: also leaves, per wavefront, the partial sums of sum_k |x - x_k|^2 and |Delta|^2
 // (App. A.3) taken from the values already in registers: no extra HBM reads.
 // OADAM: OuterOPT = AdamW (a compile-time switch: as a run-time one it slowed the SGD-family

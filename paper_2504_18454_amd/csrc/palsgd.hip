@@ -29,9 +29,10 @@
 //                  (Nesterov) momentum, restart of the K workers; optionally the
 //                  consensus-distance diagnostics from the values already in registers.
 //   restart_rows_kernel
-//                  the restart of the K workers as a launch of its own, used from K = 32 up:
-//                  short store-only wavefronts fill the rows faster than a reducing
-//                  wavefront that has K stores to issue.
+//                  the restart of the K workers as a launch of its own, used from K = 24 up
+//                  while the global model fits the memory-side cache: short store-only
+//                  wavefronts fill the rows faster than a reducing wavefront that has K
+//                  stores to issue.
 //   init_kernel    x_k^(0) <- x^(0), cleared optimizer state.
 //   ddp_kernel     DDP step of the warm-up phase: K-way gradient mean + one InnerOPT step.
 //   plan_kernel    device-resident schedule (draws, step counts, bias corrections) for
@@ -345,10 +346,18 @@ palsgd_status alloc_device_state(palsgd_ctx* c) {
     return PALSGD_OK;
 }
 
-// From this many workers on the outer step and the fused synchronisation step leave the K row stores to a
-// second launch (measured: one launch is ahead up to K = 16, the two launches by 12 % at K = 24 and 20 % at K = 64;
-// between 17 and 31 it depends on whether the global model still fits the caches, so the switch sits at 32).
-constexpr uint32_t kSplitOuterFromK = 32;
+// When the outer step, the fused synchronisation step and the DDP step leave the K row stores to a second launch:
+// from 24 workers on, and only while the global model, which that launch re-reads once per group of rows, is
+// served by the 256 MB memory-side cache (rows up to 192 MiB).  Measured through the library: at 16-192 MiB rows the
+// two launches are ahead by 4-8 % at K = 24, 8-10 % at K = 32 and 12-18 % at K = 48-64, level at K = 20; at 256 MiB rows
+// and beyond the re-reads come from DRAM and one launch is ahead by 2-10 % for every K up to 64.
+constexpr uint32_t kSplitOuterFromK = 24;
+constexpr uint64_t kSplitOuterMaxRowBytes = 192ull << 20;
+
+bool restart_apart(const palsgd_ctx* c) {
+    if (c->outer_variant == 3) return true;
+    return c->outer_variant == 0 && c->cfg.K >= kSplitOuterFromK && c->P_padded * sizeof(float) <= kSplitOuterMaxRowBytes;
+}
 
 // X[k] <- XG for all k as short wavefronts, one group of rows after the other, 16 resident per CU.
 void launch_restart_rows(palsgd_ctx* c, hipStream_t st) {
@@ -514,7 +523,7 @@ void launch_sync_step(palsgd_ctx* c, const StepArgs& args, const float* clip, co
     const palsgd_buffers& b = c->buf;
     const uint32_t lds = lds_cap(waves, 0);
     const bool oadam = c->cfg.outer_opt == PALSGD_OUTER_ADAMW;
-    const bool split = c->outer_variant == 3 || (c->outer_variant == 0 && K >= kSplitOuterFromK);
+    const bool split = restart_apart(c);
 #define PALSGD_SYNC(TAB, OADAM, tab)                                                                               \
     if (split)                                                                                                     \
         sync_step_kernel<INNER, GDT, TAB, OADAM, false><<<tile_count(c), kWave, lds, st>>>(                        \
@@ -724,9 +733,10 @@ static palsgd_status outer_impl(palsgd_ctx* ctx, const char* who, uint64_t t, fl
     const uint64_t n = ctx->P_padded;
     hipStream_t st = (hipStream_t)stream;
     const uint32_t variant = ctx->outer_variant ? ctx->outer_variant : 1u;
-    // One launch up to K = 31 (rows go 8 at a time; 4 resident wavefronts per CU are best from K = 16 up).  From
-    // K = 32 up (or variant 3) two: the reduction with OuterOPT, 6 wavefronts per CU, then the restart of the rows.
-    const bool split = ctx->outer_variant == 3 || (ctx->outer_variant == 0 && K >= kSplitOuterFromK);
+    // One launch (rows go 8 at a time; 4 resident wavefronts per CU are best from K = 16 up), or, for many workers
+    // and a global model that fits the memory-side cache (restart_apart; or variant 3), two: the reduction with
+    // OuterOPT, 6 wavefronts per CU, then the restart of the rows.
+    const bool split = restart_apart(ctx);
     const uint32_t waves = ctx->outer_waves ? ctx->outer_waves : (split ? 6u : auto_waves((8u * K + 16u) * kTile, 4));
     const palsgd_buffers& b = ctx->buf;
     const bool oadam = ctx->cfg.outer_opt == PALSGD_OUTER_ADAMW;
@@ -829,7 +839,7 @@ static palsgd_status ddp_impl(palsgd_ctx* ctx, const char* who, float alpha_t, c
     const uint32_t tiles = (uint32_t)((n + kTile - 1) / kTile);
     // rows of X this launch stores: all K, or none when the model stays shared (it is then XG alone) and when
     // the rows are many enough for a restart launch of their own to be faster (as in the outer step)
-    const bool rows_apart = !share_model && K >= kSplitOuterFromK;
+    const bool rows_apart = !share_model && restart_apart(ctx);
     const uint32_t x_rows = share_model || rows_apart ? 0u : K;
     const uint32_t per_elem = (adamw ? 24u : 16u) + 4u * x_rows + K * (bf16 ? 2u : 4u);
     const uint32_t lds = lds_cap(ctx->outer_waves ? ctx->outer_waves : auto_waves(per_elem * kTile, 4), 0);

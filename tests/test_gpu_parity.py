@@ -501,8 +501,8 @@ def test_fused_sync_step_equals_step_plus_outer(inner, grad_dtype, K):
 
 @pytest.mark.parametrize("K,inner", [(5, "adamw"), (40, "sgdm")])
 def test_outer_step_in_one_launch_and_in_two_is_the_same(K, inner):
-    """Variant 3 (reduction + OuterOPT, then the restart of the K rows as a launch of its own; the default from
-    K = 32 up) against variant 1 (everything in one launch): same sums in the same order, so the same bits, for the
+    """Variant 3 (reduction + OuterOPT, then the restart of the K rows as a launch of its own; the default for
+    many workers) against variant 1 (everything in one launch): same sums in the same order, so the same bits, for the
     outer step, the outer step with diagnostics and the fused synchronisation step; a ragged last row group
     (K = 5 and 40 are not multiples of the eight rows a restart wavefront stores)."""
     kw = dict(K=K, numels=RAGGED, inner=inner, p=0.3, H=2, seed=200 + K, sigma=0.05, row_extra=1)
